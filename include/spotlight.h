@@ -1,0 +1,167 @@
+/*
+ * spotlight.h - C ABI of the Spotlight Attention decode hot path for AMD MI355X (gfx950).
+ *
+ * Per layer and per decode step the path is (paper: Sec. 3.1 Eq. 1-2, Sec. 3.2 Eq. 3-6, appendix
+ * "Bit-Packing CUDA Kernel"):
+ *
+ *   1. hash      c = pack(sign(W2 SiLU(W1 x + b1)))   for the query and for each new key
+ *   2. retrieve  Hamming distance (XOR + popcount) of the query code to every cached key code of
+ *                the head, then the k nearest tokens per query head
+ *   3. attend    softmax attention over exactly the gathered K/V rows
+ *
+ * Conventions for every entry point
+ *   - All tensor arguments are DEVICE pointers owned by the caller, dense and contiguous in the
+ *     layout written next to them.  The library never frees, resizes or keeps them after the call.
+ *   - Work is enqueued on the HIP stream given at creation (or by spotlight_set_stream) and the
+ *     call returns without waiting for it.  spotlight_create, spotlight_destroy and
+ *     spotlight_profile_read are the only calls that synchronise.
+ *   - Return value: SPOTLIGHT_OK (0) or a negative SPOTLIGHT_ERR_* code.  Arguments are checked
+ *     on the host before the first HIP call, so argument errors never touch the GPU.
+ *   - One context must not be used from two threads at once; calls that overlap on one context
+ *     share its workspace and race.
+ *
+ * Symbols: d = head_dim (128), B = batch, Hq / Hkv = query / key-value heads, G = Hq / Hkv,
+ * L = code_bits, W = L / 32, h = hidden, Nmax = max_tokens.  Query head hq reads key-value head
+ * (and hash weights) hq / G.
+ */
+#ifndef SPOTLIGHT_H
+#define SPOTLIGHT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct spotlight_ctx spotlight_ctx; /* opaque; owns only its workspace and timing events */
+
+enum { SPOTLIGHT_F32 = 0, SPOTLIGHT_BF16 = 1 };
+
+enum {
+    SPOTLIGHT_OK = 0,
+    SPOTLIGHT_ERR_INVALID_ARG = -1, /* null pointer, size out of range, inconsistent shapes  */
+    SPOTLIGHT_ERR_UNSUPPORTED = -2, /* a well-formed request outside what the kernels cover  */
+    SPOTLIGHT_ERR_WORKSPACE = -3,   /* workspace allocation failed                           */
+    SPOTLIGHT_ERR_HIP = -4          /* a HIP runtime call or kernel launch reported an error */
+};
+
+/* Kernel stages, for spotlight_profile_read. */
+enum {
+    SPOTLIGHT_STAGE_HASH_KEYS = 0,  /* hash + pack of key rows                     */
+    SPOTLIGHT_STAGE_HASH_QUERY = 1, /* hash + pack of the query vectors            */
+    SPOTLIGHT_STAGE_SCORE = 2,      /* Hamming distances + per-block histograms    */
+    SPOTLIGHT_STAGE_SCAN = 3,       /* threshold and output offsets per head       */
+    SPOTLIGHT_STAGE_SELECT = 4,     /* ordered compaction of the selected indices  */
+    SPOTLIGHT_STAGE_ATTEND = 5,     /* gather + partial softmax attention          */
+    SPOTLIGHT_STAGE_MERGE = 6,      /* merge of the partial results                */
+    SPOTLIGHT_STAGE_COUNT = 7
+};
+
+typedef struct {
+    int32_t batch;        /* B  >= 1                                                     */
+    int32_t n_q_heads;    /* Hq >= 1, multiple of n_kv_heads, Hq / Hkv <= 8              */
+    int32_t n_kv_heads;   /* Hkv >= 1                                                    */
+    int32_t head_dim;     /* d; only 128 is supported                                    */
+    int32_t code_bits;    /* L; multiple of 32 in [32, 512]                              */
+    int32_t hidden;       /* h in [0, 4096]; 0 selects the linear hash sign(xR), Eq. 4   */
+    int64_t max_tokens;   /* Nmax: token capacity = row stride of K, V and codes         */
+    int32_t max_topk;     /* largest k any call will pass, 1 <= max_topk <= max_tokens   */
+    int32_t kv_dtype;     /* SPOTLIGHT_F32 or SPOTLIGHT_BF16: element type of q, K, V    */
+    int32_t weight_dtype; /* SPOTLIGHT_F32 or SPOTLIGHT_BF16: element type of W1, b1, W2 */
+    void *stream;         /* hipStream_t of the caller (NULL = the default stream)       */
+} spotlight_config;
+
+/* Hash MLP parameters (Eq. 5), device pointers, one MLP per key-value head, shared by the keys of
+ * that head and by the G query heads that read it.
+ *   hidden > 0 : w1 [Hkv, h, d], b1 [Hkv, h], w2 [Hkv, L, h]   (row = output unit)
+ *   hidden == 0: w1 = R stored as [Hkv, L, d] (row = hash output), b1 = w2 = NULL      (Eq. 4) */
+typedef struct {
+    const void *w1;
+    const void *b1;
+    const void *w2;
+} spotlight_hash_weights;
+
+/* Checks a configuration on the host only (no HIP call).  SPOTLIGHT_OK if spotlight_create would
+ * accept it. */
+int spotlight_validate_config(const spotlight_config *cfg);
+
+/* Bytes of device workspace spotlight_create allocates for cfg; 0 if cfg is invalid.  Host only. */
+size_t spotlight_workspace_bytes(const spotlight_config *cfg);
+
+/* Allocates the context and its device workspace on the current device.  *out is set only on
+ * success.  The workspace holds the query codes, one distance per (query head, token), per-block
+ * histograms, and the partial attention results. */
+int spotlight_create(spotlight_ctx **out, const spotlight_config *cfg);
+
+/* Waits for the stream, frees the workspace and the context.  NULL is accepted. */
+int spotlight_destroy(spotlight_ctx *ctx);
+
+/* Changes the stream later calls enqueue on. */
+int spotlight_set_stream(spotlight_ctx *ctx, void *stream);
+
+/* Static text for a return code. */
+const char *spotlight_strerror(int rc);
+
+/*
+ * Hash the key rows [t0, t0 + n_new) of every (batch, key-value head) and write their packed
+ * codes into the code cache: the append of a decode step (n_new = 1) or the bulk build after
+ * prefill.  Eq. 5-6 (Eq. 4 if hidden == 0), then bit-packing: hash output c*W + j of a key lands
+ * in word j, bit 31 - c (appendix "Bit-Packing CUDA Kernel").  sign(y) is the bit (y > 0).
+ * The arithmetic is IEEE binary32 with one fused multiply-add chain per output in increasing
+ * index order, so codes do not depend on launch shape.
+ *
+ *   K      [B, Hkv, Nmax, d]  kv_dtype   read rows t0 .. t0+n_new-1 of every head
+ *   codes  [B, Hkv, Nmax, W]  uint32     those rows written, all others untouched
+ * Errors: INVALID_ARG for NULL pointers, t0 < 0, n_new < 0 or t0 + n_new > Nmax (n_new = 0 is a
+ * no-op); missing b1 / w2 with hidden > 0.
+ */
+int spotlight_hash_keys(spotlight_ctx *ctx, const void *K, const spotlight_hash_weights *w,
+                        int64_t t0, int64_t n_new, uint32_t *codes);
+
+/*
+ * Hash the queries (Eq. 5-6), score every cached key code of the head by Hamming distance
+ * (Eq. 3: the paper's NXOR/popcount score is L minus this distance) and select, per query head,
+ * the k tokens of smallest distance; equal distances are resolved towards the lower token index.
+ *
+ *   q          [B, Hq, d]         kv_dtype
+ *   codes      [B, Hkv, Nmax, W]  uint32   rows 0 .. n_tokens-1 are read
+ *   out_idx    [B, Hq, k]         int32    selected token indices in increasing order
+ *   out_qcode  [B, Hq, W]         uint32   the query codes, or NULL
+ *   out_dist   [B, Hq, n_tokens]  uint16   every distance (debugging / tests), or NULL
+ * Errors: INVALID_ARG unless 1 <= n_tokens <= Nmax and 1 <= k <= min(n_tokens, max_topk).
+ */
+int spotlight_retrieve_topk(spotlight_ctx *ctx, const void *q, const spotlight_hash_weights *w,
+                            const uint32_t *codes, int64_t n_tokens, int32_t k,
+                            int32_t *out_idx, uint32_t *out_qcode, uint16_t *out_dist);
+
+/*
+ * Attention over exactly the rows listed in idx (Eq. 2 gather, then Eq. 1 restricted to the
+ * gathered rows; the current token takes part only if its index is listed):
+ *   out[b,hq] = sum_i softmax_i(scale * <q[b,hq], K[b,hq/G,idx_i]>) V[b,hq/G,idx_i]
+ * with binary32 accumulation.  Entries of idx outside [0, Nmax) are skipped.
+ *
+ *   q    [B, Hq, d]         kv_dtype
+ *   K,V  [B, Hkv, Nmax, d]  kv_dtype
+ *   idx  [B, Hq, k]         int32      any order; duplicates count twice
+ *   out  [B, Hq, d]         float32
+ * Errors: INVALID_ARG unless 1 <= k <= max_topk.
+ */
+int spotlight_sparse_decode(spotlight_ctx *ctx, const void *q, const void *K, const void *V,
+                            const int32_t *idx, int32_t k, float scale, float *out);
+
+/*
+ * Stage timing for benchmarks.  While enabled, every kernel launch is bracketed by two HIP events
+ * on the context's stream.  spotlight_profile_read waits for the stream, adds the elapsed times of
+ * the launches recorded since the last read to the per-stage totals and returns the totals for
+ * `stage` (milliseconds, number of launches).  spotlight_profile_enable(ctx, 0) stops recording
+ * and clears the totals.  At most 8192 launches are recorded between two reads; later ones are
+ * not timed.
+ */
+int spotlight_profile_enable(spotlight_ctx *ctx, int on);
+int spotlight_profile_read(spotlight_ctx *ctx, int stage, double *total_ms, int64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPOTLIGHT_H */

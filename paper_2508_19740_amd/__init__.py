@@ -1,0 +1,11 @@
+"""Spotlight Attention decode hot path for AMD MI355X (gfx950): hash -> retrieve -> sparse attention.
+
+The work is done by hand-written HIP kernels in libspotlight.so (C ABI: include/spotlight.h);
+this package is the thin Python binding over it.  Importing `binding` fails if the library has not
+been built; there is no CPU or eager fallback.
+"""
+from .binding import (  # noqa: F401
+    Spotlight, SpotlightError, Config, HashWeights, make_config, validate_config, workspace_bytes,
+    token_budget, spotlight_hash_keys, spotlight_retrieve_topk, spotlight_sparse_decode, lib, SYMBOLS,
+    STAGES, OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, F32, BF16,
+)

@@ -1,0 +1,291 @@
+// C ABI of libspotlight: argument checks (host only, before any HIP call), the context and its
+// workspace, stage timing, and the three calls of the decode step.
+#include <new>
+#include <string.h>
+
+#include "internal.h"
+
+namespace spotlight {
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int make_plan(const spotlight_config* c, Plan* p)
+{
+    if (!c) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (c->n_q_heads % c->n_kv_heads != 0) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (c->code_bits < 32 || c->code_bits > 512 || c->code_bits % 32 != 0) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (c->hidden < 0 || c->hidden > 4096) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (c->max_tokens < 1 || c->max_tokens > 0x7fffffffLL) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (c->max_topk < 1 || c->max_topk > c->max_tokens) return SPOTLIGHT_ERR_INVALID_ARG;
+    if ((c->kv_dtype != SPOTLIGHT_F32 && c->kv_dtype != SPOTLIGHT_BF16) ||
+        (c->weight_dtype != SPOTLIGHT_F32 && c->weight_dtype != SPOTLIGHT_BF16))
+        return SPOTLIGHT_ERR_INVALID_ARG;
+    if (c->head_dim != kHeadDim) return SPOTLIGHT_ERR_UNSUPPORTED;
+    const int G = c->n_q_heads / c->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return SPOTLIGHT_ERR_UNSUPPORTED;
+    if (c->hidden % 8 != 0) return SPOTLIGHT_ERR_UNSUPPORTED;
+    if (static_cast<int64_t>(c->batch) * c->n_q_heads > 65535) return SPOTLIGHT_ERR_UNSUPPORTED;
+
+    p->B = c->batch;
+    p->Hq = c->n_q_heads;
+    p->Hkv = c->n_kv_heads;
+    p->G = G;
+    p->L = c->code_bits;
+    p->W = c->code_bits / 32;
+    p->hidden = c->hidden;
+    p->Nmax = c->max_tokens;
+    p->max_topk = c->max_topk;
+    p->kv_dtype = c->kv_dtype;
+    p->w_dtype = c->weight_dtype;
+
+    // Tokens per score/select workgroup: 4096 (256 threads x 16) unless that leaves the chip with
+    // fewer than ~1024 workgroups, then down to 1024.
+    int tpb = 4096;
+    const int64_t kv_heads = static_cast<int64_t>(p->B) * p->Hkv;
+    while (tpb > 1024 && kv_heads * ((p->Nmax + tpb - 1) / tpb) < 1024) tpb >>= 1;
+    p->tokens_per_block = tpb;
+    p->max_blocks = static_cast<int>((p->Nmax + tpb - 1) / tpb);
+    p->dist_bytes = p->L < 256 ? 1 : 2;
+    p->dist_stride = static_cast<int64_t>(align_up(static_cast<size_t>(p->Nmax), 64));
+    p->max_splits = (p->max_topk + kAttendMinRows - 1) / kAttendMinRows;
+
+    const size_t BH = static_cast<size_t>(p->B) * p->Hq;
+    size_t off = 0;
+    p->off_qcode = off;     off = align_up(off + BH * p->W * 4, 256);
+    p->off_dist = off;      off = align_up(off + BH * static_cast<size_t>(p->dist_stride) * p->dist_bytes, 256);
+    p->off_blockhist = off; off = align_up(off + BH * p->max_blocks * static_cast<size_t>(p->L + 1) * 4, 256);
+    p->off_blockinfo = off; off = align_up(off + BH * p->max_blocks * 8, 256);
+    p->off_headinfo = off;  off = align_up(off + BH * 8, 256);
+    p->off_part_ml = off;   off = align_up(off + BH * p->max_splits * 8, 256);
+    p->off_part_acc = off;  off = align_up(off + BH * p->max_splits * static_cast<size_t>(kHeadDim) * 4, 256);
+    p->total_bytes = off;
+    return SPOTLIGHT_OK;
+}
+
+StageTimer::StageTimer(spotlight_ctx* c, int stage) : ctx(c), rec(nullptr)
+{
+    if (!c->profiling || c->n_rec >= kMaxProfile) return;
+    ProfileRec* r = &c->recs[c->n_rec];
+    if (c->n_rec >= c->n_events) {
+        if (hipEventCreate(&r->start) != hipSuccess) return;
+        if (hipEventCreate(&r->stop) != hipSuccess) { (void)hipEventDestroy(r->start); return; }
+        c->n_events = c->n_rec + 1;
+    }
+    r->stage = stage;
+    if (hipEventRecord(r->start, c->stream) != hipSuccess) return;
+    rec = r;
+}
+
+StageTimer::~StageTimer()
+{
+    if (!rec) return;
+    (void)hipEventRecord(rec->stop, ctx->stream);
+    ctx->n_rec += 1;
+}
+
+static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+static int check_weights(const spotlight_ctx* ctx, const spotlight_hash_weights* w)
+{
+    if (!w || !w->w1) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (ctx->plan.hidden > 0 && (!w->b1 || !w->w2)) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (misaligned(w->w1) || (ctx->plan.hidden > 0 && misaligned(w->w2))) return SPOTLIGHT_ERR_INVALID_ARG;
+    return SPOTLIGHT_OK;
+}
+
+}  // namespace spotlight
+
+using namespace spotlight;
+
+extern "C" {
+
+int spotlight_validate_config(const spotlight_config* cfg)
+{
+    Plan p;
+    return make_plan(cfg, &p);
+}
+
+size_t spotlight_workspace_bytes(const spotlight_config* cfg)
+{
+    Plan p;
+    if (make_plan(cfg, &p) != SPOTLIGHT_OK) return 0;
+    return p.total_bytes;
+}
+
+const char* spotlight_strerror(int rc)
+{
+    switch (rc) {
+    case SPOTLIGHT_OK: return "ok";
+    case SPOTLIGHT_ERR_INVALID_ARG: return "invalid argument";
+    case SPOTLIGHT_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SPOTLIGHT_ERR_WORKSPACE: return "workspace allocation failed";
+    case SPOTLIGHT_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error";
+    }
+}
+
+int spotlight_create(spotlight_ctx** out, const spotlight_config* cfg)
+{
+    if (!out) return SPOTLIGHT_ERR_INVALID_ARG;
+    Plan plan;
+    const int rc = make_plan(cfg, &plan);
+    if (rc != SPOTLIGHT_OK) return rc;
+    spotlight_ctx* ctx = new (std::nothrow) spotlight_ctx;
+    if (!ctx) return SPOTLIGHT_ERR_WORKSPACE;
+    memset(ctx, 0, sizeof(*ctx));
+    ctx->cfg = *cfg;
+    ctx->plan = plan;
+    ctx->stream = static_cast<hipStream_t>(cfg->stream);
+    ctx->recs = new (std::nothrow) ProfileRec[kMaxProfile];
+    if (!ctx->recs) { delete ctx; return SPOTLIGHT_ERR_WORKSPACE; }
+    int dev = 0, lds = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) {
+        delete[] ctx->recs;
+        delete ctx;
+        return SPOTLIGHT_ERR_HIP;
+    }
+    ctx->max_lds = lds;
+    void* ws = nullptr;
+    if (hipMalloc(&ws, plan.total_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        delete[] ctx->recs;
+        delete ctx;
+        return SPOTLIGHT_ERR_WORKSPACE;
+    }
+    ctx->workspace = static_cast<char*>(ws);
+    *out = ctx;
+    return SPOTLIGHT_OK;
+}
+
+int spotlight_destroy(spotlight_ctx* ctx)
+{
+    if (!ctx) return SPOTLIGHT_OK;
+    int rc = hip_rc(hipStreamSynchronize(ctx->stream));
+    for (int i = 0; i < ctx->n_events; ++i) {
+        (void)hipEventDestroy(ctx->recs[i].start);
+        (void)hipEventDestroy(ctx->recs[i].stop);
+    }
+    if (ctx->workspace && hipFree(ctx->workspace) != hipSuccess) rc = SPOTLIGHT_ERR_HIP;
+    delete[] ctx->recs;
+    delete ctx;
+    return rc;
+}
+
+int spotlight_set_stream(spotlight_ctx* ctx, void* stream)
+{
+    if (!ctx) return SPOTLIGHT_ERR_INVALID_ARG;
+    ctx->stream = static_cast<hipStream_t>(stream);
+    return SPOTLIGHT_OK;
+}
+
+int spotlight_hash_keys(spotlight_ctx* ctx, const void* K, const spotlight_hash_weights* w, int64_t t0,
+                        int64_t n_new, uint32_t* codes)
+{
+    if (!ctx || !K || !codes) return SPOTLIGHT_ERR_INVALID_ARG;
+    const Plan& p = ctx->plan;
+    int rc = check_weights(ctx, w);
+    if (rc != SPOTLIGHT_OK) return rc;
+    if (t0 < 0 || n_new < 0 || t0 > p.Nmax || n_new > p.Nmax - t0) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (misaligned(K) || misaligned(codes)) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (n_new == 0) return SPOTLIGHT_OK;
+    HashLaunch h;
+    h.x = K;
+    h.x_dtype = p.kv_dtype;
+    h.x_head_stride = p.Nmax * kHeadDim;
+    h.x_row0 = t0;
+    h.n_rows = n_new;
+    h.n_xheads = p.B * p.Hkv;
+    h.heads_per_batch = p.Hkv;
+    h.group = 1;
+    h.w1 = w->w1;
+    h.b1 = w->b1;
+    h.w2 = w->w2;
+    h.w_dtype = p.w_dtype;
+    h.hidden = p.hidden;
+    h.L = p.L;
+    h.codes = codes;
+    h.code_head_stride = p.Nmax * p.W;
+    h.code_row0 = t0;
+    return launch_hash(ctx, h, SPOTLIGHT_STAGE_HASH_KEYS);
+}
+
+int spotlight_retrieve_topk(spotlight_ctx* ctx, const void* q, const spotlight_hash_weights* w,
+                            const uint32_t* codes, int64_t n_tokens, int32_t k, int32_t* out_idx,
+                            uint32_t* out_qcode, uint16_t* out_dist)
+{
+    if (!ctx || !q || !codes || !out_idx) return SPOTLIGHT_ERR_INVALID_ARG;
+    const Plan& p = ctx->plan;
+    int rc = check_weights(ctx, w);
+    if (rc != SPOTLIGHT_OK) return rc;
+    if (n_tokens < 1 || n_tokens > p.Nmax) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (k < 1 || k > n_tokens || k > p.max_topk) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (misaligned(q) || misaligned(codes)) return SPOTLIGHT_ERR_INVALID_ARG;
+
+    HashLaunch h;
+    h.x = q;
+    h.x_dtype = p.kv_dtype;
+    h.x_head_stride = kHeadDim;
+    h.x_row0 = 0;
+    h.n_rows = 1;
+    h.n_xheads = p.B * p.Hq;
+    h.heads_per_batch = p.Hq;
+    h.group = p.G;
+    h.w1 = w->w1;
+    h.b1 = w->b1;
+    h.w2 = w->w2;
+    h.w_dtype = p.w_dtype;
+    h.hidden = p.hidden;
+    h.L = p.L;
+    h.codes = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_qcode);
+    h.code_head_stride = p.W;
+    h.code_row0 = 0;
+    rc = launch_hash(ctx, h, SPOTLIGHT_STAGE_HASH_QUERY);
+    if (rc != SPOTLIGHT_OK) return rc;
+    if (out_qcode) {
+        if (hipMemcpyAsync(out_qcode, ctx->workspace + p.off_qcode, static_cast<size_t>(p.B) * p.Hq * p.W * 4,
+                           hipMemcpyDeviceToDevice, ctx->stream) != hipSuccess)
+            return SPOTLIGHT_ERR_HIP;
+    }
+    return launch_retrieve(ctx, codes, n_tokens, k, out_idx, out_dist);
+}
+
+int spotlight_sparse_decode(spotlight_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* idx,
+                            int32_t k, float scale, float* out)
+{
+    if (!ctx || !q || !K || !V || !idx || !out) return SPOTLIGHT_ERR_INVALID_ARG;
+    const Plan& p = ctx->plan;
+    if (k < 1 || k > p.max_topk) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (misaligned(q) || misaligned(K) || misaligned(V)) return SPOTLIGHT_ERR_INVALID_ARG;
+    return launch_attend(ctx, q, K, V, idx, k, scale, out);
+}
+
+int spotlight_profile_enable(spotlight_ctx* ctx, int on)
+{
+    if (!ctx) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SPOTLIGHT_ERR_HIP;
+    ctx->profiling = on ? 1 : 0;
+    ctx->n_rec = 0;
+    for (int s = 0; s < SPOTLIGHT_STAGE_COUNT; ++s) { ctx->stage_ms[s] = 0.0; ctx->stage_launches[s] = 0; }
+    return SPOTLIGHT_OK;
+}
+
+int spotlight_profile_read(spotlight_ctx* ctx, int stage, double* total_ms, int64_t* launches)
+{
+    if (!ctx || stage < 0 || stage >= SPOTLIGHT_STAGE_COUNT) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return SPOTLIGHT_ERR_HIP;
+    int rc = SPOTLIGHT_OK;
+    for (int i = 0; i < ctx->n_rec; ++i) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, ctx->recs[i].start, ctx->recs[i].stop) != hipSuccess) { rc = SPOTLIGHT_ERR_HIP; continue; }
+        ctx->stage_ms[ctx->recs[i].stage] += ms;
+        ctx->stage_launches[ctx->recs[i].stage] += 1;
+    }
+    ctx->n_rec = 0;
+    if (total_ms) *total_ms = ctx->stage_ms[stage];
+    if (launches) *launches = ctx->stage_launches[stage];
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,237 @@
+// Gather + sparse attention (paper Sec. 3.1: Eq. 2 gather, Eq. 1 restricted to the gathered rows).
+//
+// The work of one query head (k scattered rows of K and of V, 256 or 512 bytes each) is split over
+// ceil(k / RB) workgroups so that a few dozen heads still fill 256 compute units.  A row is read
+// by LPR adjacent lanes, 16 bytes per lane, so a wavefront fetches 64 / LPR whole rows per load
+// instruction.  A wavefront first issues the loads of ALL its K rows and V rows (up to 16 KB in
+// flight per wave: the kernel is bound by random-row HBM latency x bandwidth, not arithmetic),
+// then forms the scores, a wave-local softmax in binary32, and the weighted sum of its V rows.
+// Workgroup partials (max, sum, acc[128]) go to the workspace and a small second kernel merges
+// the partials of each head with the usual max-rescaling.
+#include "internal.h"
+
+namespace spotlight {
+namespace {
+
+struct bf16_raw { uint16_t v; };
+
+template <typename T> struct RowTraits;
+template <> struct RowTraits<bf16_raw> { static constexpr int kLanesPerRow = 16, kElems = 8; };
+template <> struct RowTraits<float> { static constexpr int kLanesPerRow = 32, kElems = 4; };
+
+template <typename T>
+__device__ __forceinline__ void unpack(const uint4& u, float (&o)[RowTraits<T>::kElems])
+{
+    if constexpr (sizeof(T) == 2) {
+        o[0] = __uint_as_float(u.x << 16); o[1] = __uint_as_float(u.x & 0xffff0000u);
+        o[2] = __uint_as_float(u.y << 16); o[3] = __uint_as_float(u.y & 0xffff0000u);
+        o[4] = __uint_as_float(u.z << 16); o[5] = __uint_as_float(u.z & 0xffff0000u);
+        o[6] = __uint_as_float(u.w << 16); o[7] = __uint_as_float(u.w & 0xffff0000u);
+    } else {
+        o[0] = __uint_as_float(u.x); o[1] = __uint_as_float(u.y);
+        o[2] = __uint_as_float(u.z); o[3] = __uint_as_float(u.w);
+    }
+}
+
+// RB rows per workgroup, RB / 4 per wavefront.
+template <typename T, int RB>
+__global__ __launch_bounds__(kThreads) void attend_kernel(
+    const T* __restrict__ q, const T* __restrict__ K, const T* __restrict__ V, const int32_t* __restrict__ idx,
+    float2* __restrict__ part_ml, float* __restrict__ part_acc, int k, float scale, int64_t Nmax, int Hq, int Hkv,
+    int nsplit, int max_splits)
+{
+    constexpr int LPR = RowTraits<T>::kLanesPerRow;   // lanes per row
+    constexpr int E = RowTraits<T>::kElems;           // elements per lane
+    constexpr int RPI = 64 / LPR;                     // rows per load instruction
+    constexpr int RPW = RB / 4;                       // rows per wave
+    constexpr int ITERS = RPW / RPI;
+    static_assert(RPW % RPI == 0 && RPW <= 64, "row tiling");
+
+    __shared__ float s_m[4], s_l[4];
+    __shared__ float s_acc[4][kHeadDim];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int split = blockIdx.x;
+    const int64_t bh = blockIdx.y;
+    const int b = static_cast<int>(bh / Hq), hq = static_cast<int>(bh % Hq);
+    const int hk = hq / (Hq / Hkv);
+    const int sub = lane % LPR, grp = lane / LPR;
+
+    const T* Kh = K + (static_cast<int64_t>(b) * Hkv + hk) * Nmax * kHeadDim;
+    const T* Vh = V + (static_cast<int64_t>(b) * Hkv + hk) * Nmax * kHeadDim;
+
+    // this lane's slice of q
+    float qf[E];
+    {
+        const uint4 u = *reinterpret_cast<const uint4*>(q + bh * kHeadDim + sub * E);
+        unpack<T>(u, qf);
+    }
+
+    // row indices of this wave: lane i holds row (row0 + i)
+    const int row0 = split * RB + wave * RPW;
+    int my_idx = -1;
+    if (lane < RPW && row0 + lane < k) {
+        const int v = idx[bh * k + row0 + lane];
+        if (v >= 0 && static_cast<int64_t>(v) < Nmax) my_idx = v;
+    }
+
+    uint4 kr[ITERS], vr[ITERS];
+    int ridx[ITERS];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        ridx[it] = __shfl(my_idx, it * RPI + grp);
+        if (ridx[it] >= 0) {
+            const int64_t off = static_cast<int64_t>(ridx[it]) * kHeadDim + sub * E;
+            kr[it] = *reinterpret_cast<const uint4*>(Kh + off);
+        } else {
+            kr[it] = make_uint4(0, 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        if (ridx[it] >= 0) {
+            const int64_t off = static_cast<int64_t>(ridx[it]) * kHeadDim + sub * E;
+            vr[it] = *reinterpret_cast<const uint4*>(Vh + off);
+        } else {
+            vr[it] = make_uint4(0, 0, 0, 0);
+        }
+    }
+
+    // scores
+    float s[ITERS];
+    float m = -INFINITY;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        float kf[E];
+        unpack<T>(kr[it], kf);
+        float dot = 0.0f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) dot = __builtin_fmaf(qf[e], kf[e], dot);
+#pragma unroll
+        for (int off = LPR / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off);
+        s[it] = ridx[it] >= 0 ? dot * scale : -INFINITY;
+        m = fmaxf(m, s[it]);
+    }
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) m = fmaxf(m, __shfl_xor(m, off));
+
+    // wave-local softmax numerators and weighted V sum
+    float l = 0.0f;
+    float acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[e] = 0.0f;
+    if (m > -INFINITY) {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const float p = ridx[it] >= 0 ? __expf(s[it] - m) : 0.0f;
+            l += p;
+            float vf[E];
+            unpack<T>(vr[it], vf);
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] = __builtin_fmaf(p, vf[e], acc[e]);
+        }
+    }
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+        l += __shfl_xor(l, off);
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[e] += __shfl_xor(acc[e], off);
+    }
+    if (grp == 0) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) s_acc[wave][sub * E + e] = acc[e];
+    }
+    if (lane == 0) { s_m[wave] = m; s_l[wave] = l; }
+    __syncthreads();
+
+    // merge the four waves; thread c < 128 owns output column c
+    if (tid < kHeadDim) {
+        const float M = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+        float a = 0.0f, lsum = 0.0f;
+        if (M > -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float f = s_m[w] > -INFINITY ? __expf(s_m[w] - M) : 0.0f;
+                a = __builtin_fmaf(f, s_acc[w][tid], a);
+                lsum = __builtin_fmaf(f, s_l[w], lsum);
+            }
+        }
+        const int64_t pi = bh * max_splits + split;
+        part_acc[pi * kHeadDim + tid] = a;
+        if (tid == 0) part_ml[pi] = make_float2(M, lsum);
+    }
+}
+
+__global__ __launch_bounds__(kHeadDim) void merge_kernel(const float2* __restrict__ part_ml,
+                                                         const float* __restrict__ part_acc,
+                                                         float* __restrict__ out, int nsplit, int max_splits)
+{
+    const int c = threadIdx.x;
+    const int64_t bh = blockIdx.x;
+    const float2* ml = part_ml + bh * max_splits;
+    const float* pa = part_acc + bh * max_splits * kHeadDim;
+    float M = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, ml[s].x);
+    float a = 0.0f, l = 0.0f;
+    if (M > -INFINITY) {
+        for (int s = 0; s < nsplit; ++s) {
+            const float2 v = ml[s];
+            const float f = v.x > -INFINITY ? __expf(v.x - M) : 0.0f;
+            a = __builtin_fmaf(f, pa[static_cast<int64_t>(s) * kHeadDim + c], a);
+            l = __builtin_fmaf(f, v.y, l);
+        }
+    }
+    out[bh * kHeadDim + c] = l > 0.0f ? a / l : 0.0f;
+}
+
+template <typename T, int RB>
+void launch_rb(spotlight_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* idx, int k,
+               float scale, int nsplit)
+{
+    const Plan& p = ctx->plan;
+    dim3 grid(static_cast<unsigned>(nsplit), static_cast<unsigned>(p.B * p.Hq));
+    hipLaunchKernelGGL((attend_kernel<T, RB>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const T*>(q),
+                       static_cast<const T*>(K), static_cast<const T*>(V), idx,
+                       reinterpret_cast<float2*>(ctx->workspace + p.off_part_ml),
+                       reinterpret_cast<float*>(ctx->workspace + p.off_part_acc), k, scale, p.Nmax, p.Hq, p.Hkv,
+                       nsplit, p.max_splits);
+}
+
+template <typename T>
+int launch_t(spotlight_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* idx, int k,
+             float scale, float* out)
+{
+    const Plan& p = ctx->plan;
+    const int64_t heads = static_cast<int64_t>(p.B) * p.Hq;
+    // the largest row tile that still gives the chip about four workgroups per compute unit
+    int RB = 128;
+    while (RB > kAttendMinRows && heads * ((k + RB - 1) / RB) < 1024) RB >>= 1;
+    const int nsplit = (k + RB - 1) / RB;
+    {
+        StageTimer timer(ctx, SPOTLIGHT_STAGE_ATTEND);
+        if (RB == 128) launch_rb<T, 128>(ctx, q, K, V, idx, k, scale, nsplit);
+        else if (RB == 64) launch_rb<T, 64>(ctx, q, K, V, idx, k, scale, nsplit);
+        else launch_rb<T, 32>(ctx, q, K, V, idx, k, scale, nsplit);
+        if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
+    }
+    {
+        StageTimer timer(ctx, SPOTLIGHT_STAGE_MERGE);
+        hipLaunchKernelGGL(merge_kernel, dim3(static_cast<unsigned>(heads)), dim3(kHeadDim), 0, ctx->stream,
+                           reinterpret_cast<const float2*>(ctx->workspace + p.off_part_ml),
+                           reinterpret_cast<const float*>(ctx->workspace + p.off_part_acc), out, nsplit,
+                           p.max_splits);
+        if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
+    }
+    return SPOTLIGHT_OK;
+}
+
+}  // namespace
+
+int launch_attend(spotlight_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* idx, int k,
+                  float scale, float* out)
+{
+    if (ctx->plan.kv_dtype == SPOTLIGHT_BF16) return launch_t<bf16_raw>(ctx, q, K, V, idx, k, scale, out);
+    return launch_t<float>(ctx, q, K, V, idx, k, scale, out);
+}
+
+}  // namespace spotlight

@@ -1,0 +1,265 @@
+// Hash MLP + sign + bit-packing (paper Sec. 3.2 Eq. 4-6, appendix "Bit-Packing CUDA Kernel").
+//
+// One workgroup hashes a tile of TK vectors of one head.  Every output keeps its own binary32
+// accumulator and takes its fused multiply-adds in increasing index order, so the sign bits do not
+// depend on the tile size or launch shape:
+//   a_i = b1_i + sum_k W1[i][k] x[k];  h_i = a_i / (1 + exp(-a_i));  y_j = sum_i W2[j][i] h_i
+// exp is the fixed routine silu_exp() (range clamp, round-to-nearest reduction by ln 2 in two fused
+// steps, degree-7 Horner polynomial, exact power-of-two scaling).
+//
+// Phase 1: thread i owns hidden unit i (+256, ...), streams its W1 row from global memory 8 values
+//          at a time and reads x from LDS (stored [k][t], so one 16-byte LDS read feeds 4 vectors).
+// Phase 2: a wavefront owns two code words; lane l computes the hash output that belongs to bit
+//          (l & 31) of word 2p + (l >> 5), i.e. output (31 - (l & 31)) * W + word, so a wave-wide
+//          ballot of (y > 0) IS the pair of packed words.  No boolean tensor is ever stored.
+#include "internal.h"
+
+namespace spotlight {
+namespace {
+
+struct bf16_raw { uint16_t v; };
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
+
+// load 8 consecutive elements starting at p (16-byte aligned for bf16, 32-byte for f32) as floats
+__device__ __forceinline__ void load8(const float* p, float (&o)[8])
+{
+    const float4 a = reinterpret_cast<const float4*>(p)[0];
+    const float4 b = reinterpret_cast<const float4*>(p)[1];
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+    o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_raw* p, float (&o)[8])
+{
+    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    o[0] = __uint_as_float(u.x << 16); o[1] = __uint_as_float(u.x & 0xffff0000u);
+    o[2] = __uint_as_float(u.y << 16); o[3] = __uint_as_float(u.y & 0xffff0000u);
+    o[4] = __uint_as_float(u.z << 16); o[5] = __uint_as_float(u.z & 0xffff0000u);
+    o[6] = __uint_as_float(u.w << 16); o[7] = __uint_as_float(u.w & 0xffff0000u);
+}
+__device__ __forceinline__ float load1(const float* p) { return *p; }
+__device__ __forceinline__ float load1(const bf16_raw* p) { return bf16_bits_to_f32(p->v); }
+
+__device__ __forceinline__ float silu_exp(float t)
+{
+    t = (t > -87.0f) ? t : -87.0f;  // NaN goes to -87 as well
+    t = (t < 88.0f) ? t : 88.0f;
+    const float n = __builtin_rintf(t * 0x1.715476p+0f);
+    float r = __builtin_fmaf(n, -0x1.62e400p-1f, t);
+    r = __builtin_fmaf(n, -0x1.7f7d1cp-20f, r);
+    float p = 0x1.a01a02p-13f;
+    p = __builtin_fmaf(p, r, 0x1.6c16c2p-10f);
+    p = __builtin_fmaf(p, r, 0x1.111112p-7f);
+    p = __builtin_fmaf(p, r, 0x1.555556p-5f);
+    p = __builtin_fmaf(p, r, 0x1.555556p-3f);
+    p = __builtin_fmaf(p, r, 0.5f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    const float s = __uint_as_float(static_cast<uint32_t>(static_cast<int>(n) + 127) << 23);
+    return p * s;
+}
+
+__device__ __forceinline__ float silu(float a)
+{
+    const float e = silu_exp(-a);
+    const float den = 1.0f + e;
+    return a / den;  // IEEE-correct binary32 division
+}
+
+// TK consecutive floats from LDS (16-byte reads when TK is a multiple of 4)
+template <int TK>
+__device__ __forceinline__ void lds_tile(const float* p, float (&o)[TK])
+{
+    if constexpr (TK % 4 == 0) {
+#pragma unroll
+        for (int t = 0; t < TK / 4; ++t) {
+            const float4 v = reinterpret_cast<const float4*>(p)[t];
+            o[4 * t] = v.x; o[4 * t + 1] = v.y; o[4 * t + 2] = v.z; o[4 * t + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < TK; ++t) o[t] = p[t];
+    }
+}
+
+struct HashArgs {
+    const void* x;
+    int64_t x_head_stride, x_row0, n_rows;
+    int heads_per_batch, group, n_wheads;
+    const void* w1;
+    const void* b1;
+    const void* w2;
+    int hidden, L, W;
+    uint32_t* codes;
+    int64_t code_head_stride, code_row0;
+};
+
+// LDS: xs [128][TK] floats, then hs [hidden][TK] floats (hidden > 0 only).
+template <typename XT, typename WT, int TK, int KSPLIT>
+__global__ __launch_bounds__(kThreads) void hash_kernel(HashArgs a)
+{
+    extern __shared__ __align__(16) float lds[];
+    float* xs = lds;
+    float* hs = lds + kHeadDim * TK;
+
+    const int tid = threadIdx.x;
+    const int xhead = blockIdx.y;
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * TK;
+    const int rows = static_cast<int>(min(static_cast<int64_t>(TK), a.n_rows - r0));
+    const int whead = (xhead % a.heads_per_batch) / a.group;
+
+    // ---- stage the x tile, transposed to [k][t], rows past the end as zeros
+    const XT* xbase = static_cast<const XT*>(a.x) + xhead * a.x_head_stride + (a.x_row0 + r0) * kHeadDim;
+    for (int e = tid; e < TK * (kHeadDim / 8); e += kThreads) {
+        const int t = e / (kHeadDim / 8), k8 = e % (kHeadDim / 8);
+        float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (t < rows) load8(xbase + static_cast<int64_t>(t) * kHeadDim + k8 * 8, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) xs[(k8 * 8 + j) * TK + t] = v[j];
+    }
+    __syncthreads();
+
+    // ---- phase 1: hidden activations
+    const float* act = xs;   // what phase 2 contracts over
+    int act_dim = kHeadDim;
+    const WT* wout = static_cast<const WT*>(a.w1) + static_cast<int64_t>(whead) * a.L * kHeadDim;  // linear hash: R
+    if (a.hidden > 0) {
+        const WT* w1 = static_cast<const WT*>(a.w1) + static_cast<int64_t>(whead) * a.hidden * kHeadDim;
+        const WT* b1 = static_cast<const WT*>(a.b1) + static_cast<int64_t>(whead) * a.hidden;
+        for (int i = tid; i < a.hidden; i += kThreads) {
+            float acc[TK];
+            const float bias = load1(b1 + i);
+#pragma unroll
+            for (int t = 0; t < TK; ++t) acc[t] = bias;
+            const WT* row = w1 + static_cast<int64_t>(i) * kHeadDim;
+            for (int k8 = 0; k8 < kHeadDim / 8; ++k8) {
+                float wv[8];
+                load8(row + k8 * 8, wv);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    float xr[TK];
+                    lds_tile<TK>(xs + (k8 * 8 + j) * TK, xr);
+#pragma unroll
+                    for (int t = 0; t < TK; ++t) acc[t] = __builtin_fmaf(wv[j], xr[t], acc[t]);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < TK; ++t) hs[i * TK + t] = silu(acc[t]);
+        }
+        __syncthreads();
+        act = hs;
+        act_dim = a.hidden;
+        wout = static_cast<const WT*>(a.w2) + static_cast<int64_t>(whead) * a.L * a.hidden;
+    }
+
+    // ---- phase 2: outputs, sign, ballot-pack
+    constexpr int TK2 = TK / KSPLIT;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int npairs = (a.W + 1) / 2;
+    uint32_t* cbase = a.codes + xhead * a.code_head_stride + (a.code_row0 + r0) * a.W;
+    for (int item = wave; item < npairs * KSPLIT; item += kThreads / 64) {
+        const int pair = item / KSPLIT, ks = item % KSPLIT;
+        const int word = 2 * pair + (lane >> 5);
+        const bool live = word < a.W;
+        const int o = live ? (31 - (lane & 31)) * a.W + word : 0;
+        const WT* row = wout + static_cast<int64_t>(o) * act_dim;
+        float y[TK2];
+#pragma unroll
+        for (int t = 0; t < TK2; ++t) y[t] = 0.0f;
+        for (int i8 = 0; i8 < act_dim / 8; ++i8) {
+            float wv[8];
+            load8(row + i8 * 8, wv);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                float hr[TK2];
+                lds_tile<TK2>(act + (i8 * 8 + j) * TK + ks * TK2, hr);
+#pragma unroll
+                for (int t = 0; t < TK2; ++t) y[t] = __builtin_fmaf(wv[j], hr[t], y[t]);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < TK2; ++t) {
+            const unsigned long long m = __ballot(live && (y[t] > 0.0f));
+            const int r = ks * TK2 + t;
+            if (lane == 0 && r < rows) {
+                cbase[static_cast<int64_t>(r) * a.W + 2 * pair] = static_cast<uint32_t>(m);
+                if (2 * pair + 1 < a.W) cbase[static_cast<int64_t>(r) * a.W + 2 * pair + 1] = static_cast<uint32_t>(m >> 32);
+            }
+        }
+    }
+}
+
+inline size_t lds_bytes(int tk, int hidden) { return sizeof(float) * tk * (kHeadDim + hidden); }
+
+template <typename XT, typename WT, int TK, int KSPLIT>
+int run(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
+{
+    const size_t lds = lds_bytes(TK, a.hidden);
+    if (lds > static_cast<size_t>(ctx->max_lds)) return SPOTLIGHT_ERR_UNSUPPORTED;
+    auto kern = hash_kernel<XT, WT, TK, KSPLIT>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return SPOTLIGHT_ERR_HIP;
+    }
+    const int64_t tiles = (a.n_rows + TK - 1) / TK;
+    dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(n_xheads));
+    StageTimer timer(ctx, stage);
+    hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, ctx->stream, a);
+    return hip_rc(hipGetLastError());
+}
+
+template <typename XT, typename WT, int TK>
+int run_ks(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
+{
+    const int npairs = (a.W + 1) / 2;
+    if constexpr (TK >= 4) {
+        if (npairs == 1) return run<XT, WT, TK, 4>(ctx, a, n_xheads, stage);
+    }
+    if constexpr (TK >= 2) {
+        if (npairs <= 2) return run<XT, WT, TK, 2>(ctx, a, n_xheads, stage);
+    }
+    return run<XT, WT, TK, 1>(ctx, a, n_xheads, stage);
+}
+
+template <typename XT, typename WT>
+int run_tk(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
+{
+    const size_t cap = static_cast<size_t>(ctx->max_lds);
+    if (a.n_rows >= 32 && lds_bytes(32, a.hidden) <= cap) return run_ks<XT, WT, 32>(ctx, a, n_xheads, stage);
+    if (a.n_rows >= 4 && lds_bytes(8, a.hidden) <= cap) return run_ks<XT, WT, 8>(ctx, a, n_xheads, stage);
+    return run_ks<XT, WT, 1>(ctx, a, n_xheads, stage);
+}
+
+}  // namespace
+
+int launch_hash(spotlight_ctx* ctx, const HashLaunch& h, int stage)
+{
+    if (h.n_rows <= 0 || h.n_xheads <= 0) return SPOTLIGHT_OK;
+    // the weight rows are read 8 elements at a time
+    if (h.hidden % 8 != 0) return SPOTLIGHT_ERR_UNSUPPORTED;
+    HashArgs a;
+    a.x = h.x;
+    a.x_head_stride = h.x_head_stride;
+    a.x_row0 = h.x_row0;
+    a.n_rows = h.n_rows;
+    a.heads_per_batch = h.heads_per_batch;
+    a.group = h.group;
+    a.n_wheads = h.heads_per_batch / h.group;
+    a.w1 = h.w1;
+    a.b1 = h.b1;
+    a.w2 = h.w2;
+    a.hidden = h.hidden;
+    a.L = h.L;
+    a.W = h.L / 32;
+    a.codes = h.codes;
+    a.code_head_stride = h.code_head_stride;
+    a.code_row0 = h.code_row0;
+    const bool xb = h.x_dtype == SPOTLIGHT_BF16, wb = h.w_dtype == SPOTLIGHT_BF16;
+    if (xb && wb) return run_tk<bf16_raw, bf16_raw>(ctx, a, h.n_xheads, stage);
+    if (xb && !wb) return run_tk<bf16_raw, float>(ctx, a, h.n_xheads, stage);
+    if (!xb && wb) return run_tk<float, bf16_raw>(ctx, a, h.n_xheads, stage);
+    return run_tk<float, float>(ctx, a, h.n_xheads, stage);
+}
+
+}  // namespace spotlight

@@ -1,0 +1,95 @@
+// Internal declarations shared by the HIP translation units of libspotlight (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "spotlight.h"
+
+namespace spotlight {
+
+constexpr int kHeadDim = 128;
+constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts of 64 lanes per workgroup
+constexpr int kMaxGroup = 8;        // query heads per key-value head
+constexpr int kAttendMinRows = 32;  // smallest number of gathered rows one workgroup takes
+constexpr int kMaxProfile = 8192;
+
+// Geometry derived once from the configuration.
+struct Plan {
+    int B, Hq, Hkv, G, L, W, hidden;
+    int64_t Nmax;
+    int max_topk;
+    int kv_dtype, w_dtype;
+    int tokens_per_block;  // tokens one score / select workgroup covers
+    int max_blocks;        // ceil(Nmax / tokens_per_block)
+    int dist_bytes;        // 1 if L < 256 else 2
+    int64_t dist_stride;   // distances per query head in the workspace (Nmax rounded up to 64)
+    int max_splits;        // ceil(max_topk / kAttendMinRows)
+    // workspace offsets in bytes
+    size_t off_qcode, off_dist, off_blockhist, off_blockinfo, off_headinfo, off_part_ml, off_part_acc;
+    size_t total_bytes;
+};
+
+int make_plan(const spotlight_config* cfg, Plan* plan);  // SPOTLIGHT_OK or an error code; host only
+
+struct ProfileRec {
+    int stage;
+    hipEvent_t start, stop;
+};
+
+}  // namespace spotlight
+
+struct spotlight_ctx {
+    spotlight_config cfg;
+    spotlight::Plan plan;
+    hipStream_t stream;
+    char* workspace;
+    int max_lds;                     // bytes of LDS one workgroup may use on this device
+    // profiling
+    int profiling;
+    int n_rec;                       // records in use since the last read
+    int n_events;                    // event pairs created so far
+    spotlight::ProfileRec* recs;     // kMaxProfile entries
+    double stage_ms[SPOTLIGHT_STAGE_COUNT];
+    int64_t stage_launches[SPOTLIGHT_STAGE_COUNT];
+};
+
+namespace spotlight {
+
+// RAII bracket around one kernel launch: records events when profiling is on.
+struct StageTimer {
+    spotlight_ctx* ctx;
+    ProfileRec* rec;
+    StageTimer(spotlight_ctx* c, int stage);
+    ~StageTimer();
+};
+
+// Launchers (each returns SPOTLIGHT_OK or SPOTLIGHT_ERR_*).  All pointers are device pointers.
+struct HashLaunch {
+    const void* x;            // vectors to hash
+    int x_dtype;
+    int64_t x_head_stride;    // elements between consecutive x-heads
+    int64_t x_row0;           // first row inside each x-head
+    int64_t n_rows;           // rows per x-head
+    int n_xheads;             // B * (heads on the x side)
+    int heads_per_batch;      // heads on the x side per batch entry
+    int group;                // x-heads per weight head
+    const void* w1;
+    const void* b1;
+    const void* w2;
+    int w_dtype, hidden, L;
+    uint32_t* codes;
+    int64_t code_head_stride; // words between consecutive x-heads
+    int64_t code_row0;
+};
+int launch_hash(spotlight_ctx* ctx, const HashLaunch& a, int stage);
+
+int launch_retrieve(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens, int k,
+                    int32_t* out_idx, uint16_t* out_dist);
+
+int launch_attend(spotlight_ctx* ctx, const void* q, const void* K, const void* V,
+                  const int32_t* idx, int k, float scale, float* out);
+
+inline int hip_rc(hipError_t e) { return e == hipSuccess ? SPOTLIGHT_OK : SPOTLIGHT_ERR_HIP; }
+
+}  // namespace spotlight
