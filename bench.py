@@ -1,0 +1,284 @@
+#!/usr/bin/env python3
+"""Benchmark of the Spotlight decode hot path on one MI355X.
+
+A "step" is one decode step of one attention layer on synthetic, seeded inputs that are already
+resident in HBM: append-hash of one new key per head, retrieval (query hash + Hamming scoring +
+per-head top-k) and sparse attention over the selected rows.  The default workload is config C3
+(batch 1, 32 heads, 524288 cached tokens, 128-bit codes, top-k 10486, bf16 K/V), the one the
+headline metric (retrieval time at 512K tokens / 32 heads) is quoted on.
+
+Consecutive steps rotate over several independent "layers" (separate code / K / V tensors, at
+least 1 GiB of codes in total) so that the 256 MB last-level cache cannot serve the code stream:
+the numbers are HBM numbers, as in a model whose every layer is touched once per token.
+
+Output: ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="C3", help="C1 | C2 | C3 | C4 | C5-128 | C5-512")
+    ap.add_argument("--layers", type=int, default=0, help="independent layers to rotate over (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=2, help="heads in the oracle's timed sample")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; run it with --gpus 1 (no multi-GPU path exists)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workload as wl
+    import paper_2508_19740_amd as sp
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = wl.CONFIGS[args.config]
+    B, Hq, Hkv, N, L, W, k, d = (cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_tokens, cfg.code_bits,
+                                 cfg.words, cfg.topk, cfg.head_dim)
+    esz = 2 if cfg.kv_dtype == "bf16" else 4
+    kv_t = torch.bfloat16 if esz == 2 else torch.float32
+    w_t = torch.bfloat16 if cfg.weight_dtype == "bf16" else torch.float32
+    grow = cfg.extra_tokens > 0                     # C5: the cache grows by one token per step
+    code_bytes = B * Hkv * N * L // 8
+    layer_bytes = code_bytes + 2 * B * Hkv * cfg.max_tokens * d * esz
+    if args.layers > 0:
+        n_layers = args.layers
+    else:
+        n_layers = max(1, min(8, math.ceil((1 << 30) / code_bytes)))
+        while n_layers > 1 and n_layers * layer_bytes > 120 * (1 << 30):
+            n_layers -= 1
+
+    # ------------------------------------------------------------------ inputs (untimed)
+    t_setup = time.time()
+    ctx = sp.Spotlight(B, Hq, Hkv, L, cfg.hidden, cfg.max_tokens, k, kv_dtype=kv_t, weight_dtype=w_t, device=dev)
+    layers = []
+    for li in range(n_layers):
+        c = cfg.scaled(seed=cfg.seed + 1000 * li)
+        w = wl.Workload(c)
+        lay = {
+            "w": w,
+            "K": w.materialize("K", dev),
+            "V": w.materialize("V", dev),
+            "q": w.q.to(dev),
+            "weights": tuple(t.to(dev) for t in w.hash_weights()),
+            "codes": torch.zeros(B, Hkv, cfg.max_tokens, W, dtype=torch.int32, device=dev),
+            "idx": torch.empty(B, Hq, k, dtype=torch.int32, device=dev),
+            "out": torch.empty(B, Hq, d, dtype=torch.float32, device=dev),
+        }
+        layers.append(lay)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_setup
+    # bulk build of the code caches (setup, timed separately)
+    ctx.profile_enable(True)
+    for lay in layers:
+        ctx.hash_keys(lay["K"], *lay["weights"], 0, N, lay["codes"])
+    prof = ctx.profile_read()
+    bulk_ms = prof["hash_keys"][0] / max(1, prof["hash_keys"][1])
+    ctx.profile_enable(False)
+
+    def step(i, ev=None):
+        lay = layers[i % n_layers]
+        n_tok = N
+        if grow:                                    # append one key per head, then retrieve over n+1
+            j = (i // n_layers) % cfg.extra_tokens
+            ctx.hash_keys(lay["K"], *lay["weights"], N + j, 1, lay["codes"])
+            n_tok = N + j + 1
+        else:                                       # re-hash the newest key in place (same work)
+            ctx.hash_keys(lay["K"], *lay["weights"], N - 1, 1, lay["codes"])
+        if ev:
+            ev[0].record()
+        ctx.retrieve_topk(lay["q"], *lay["weights"], lay["codes"], n_tok, k, out_idx=lay["idx"])
+        if ev:
+            ev[1].record()
+        ctx.sparse_decode(lay["q"], lay["K"], lay["V"], lay["idx"], None, out=lay["out"])
+        if ev:
+            ev[2].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ------------------------------------------------------------------ timed region
+    K_steps = args.steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K_steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K_steps):
+        step(i, evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K_steps
+    retr_us = sorted(e[0].elapsed_time(e[1]) * 1e3 for e in evs)
+    att_us = sorted(e[1].elapsed_time(e[2]) * 1e3 for e in evs)
+    retrieve_us = sum(retr_us) / K_steps
+    attend_us = sum(att_us) / K_steps
+
+    # ------------------------------------------------------------------ per-kernel durations
+    # Same K steps again with every kernel launch bracketed by HIP events on the library's stream.
+    ctx.profile_enable(True)
+    stage = {name: [0.0, 0] for name in sp.STAGES}
+    done = 0
+    while done < K_steps:
+        chunk = min(K_steps - done, 512)            # at most 8192 recorded launches between reads
+        for i in range(done, done + chunk):
+            step(i)
+        for name, (ms, n) in ctx.profile_read().items():
+            stage[name] = [ms, n]
+        done += chunk
+    ctx.profile_enable(False)
+    stage_us = {name: (ms * 1e3 / n if n else None) for name, (ms, n) in stage.items()}
+
+    # ------------------------------------------------------------------ algorithmic bytes
+    # score: every key code read once (L/8 bytes per key per key-value head)
+    score_bytes = B * Hkv * N * (L // 8)
+    # retrieval as a whole: codes once + indices written + hash weights read for the queries
+    wsz = 2 if cfg.weight_dtype == "bf16" else 4
+    weight_bytes = Hkv * ((cfg.hidden * d + cfg.hidden + L * cfg.hidden) if cfg.hidden else L * d) * wsz
+    retrieve_bytes = score_bytes + B * Hq * k * 4 + weight_bytes
+    # attention: K and V row per selected token, its index, q in, out written
+    attend_bytes = B * Hq * k * (2 * d * esz + 4) + B * Hq * d * (esz + 4)
+
+    def gbps(nbytes, us):
+        return nbytes / (us * 1e-6) / 1e9 if us else None
+
+    score_us = stage_us["score"]
+    roofline = {
+        "kernel": "score_kernel (Hamming distance, histograms, candidate lists)",
+        "bound": "hbm",
+        "achieved": round(gbps(score_bytes, score_us), 1),
+        "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s",
+        "frac": round(gbps(score_bytes, score_us) / HBM_PEAK_GBPS, 4),
+        "traffic": None,
+        "bytes_per_launch": score_bytes,
+        "avg_launch_us": round(score_us, 2),
+        "timing": "HIP events around each launch, second pass over the same steps",
+    }
+    roofline_attend = {
+        "kernel": "attend_kernel (gather + softmax attention, merge by the last workgroup)",
+        "bound": "hbm",
+        "achieved": round(gbps(attend_bytes, stage_us["attend"]), 1),
+        "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s",
+        "frac": round(gbps(attend_bytes, stage_us["attend"]) / HBM_PEAK_GBPS, 4),
+        "traffic": None,
+        "bytes_per_launch": attend_bytes,
+        "avg_launch_us": round(stage_us["attend"], 2),
+    }
+
+    result = {
+        "metric": "retrieval_us_512k_tokens_32_heads" if args.config == "C3" else f"retrieval_us_{args.config}",
+        "value": round(retrieve_us, 2),
+        "unit": "us",
+        "n_gpus": 1,
+        "steps": K_steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32 xor/popcount (retrieval), f32 (hash MLP, softmax accumulate), bf16 K/V"
+                 if esz == 2 else "u32 xor/popcount (retrieval), f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: batch {B}, {Hq} q heads / {Hkv} kv heads, head_dim {d}, "
+                        f"{N} cached tokens, {L}-bit codes (MLP {d}->{cfg.hidden}->{L}), top-k {k}, "
+                        f"{cfg.kv_dtype} K/V",
+            "layers_rotated": n_layers,
+            "step": "append-hash 1 key/head + retrieve_topk + sparse_decode",
+        },
+        "retrieve_us": {"mean": round(retrieve_us, 2), "median": round(retr_us[K_steps // 2], 2),
+                        "min": round(retr_us[0], 2)},
+        "attend_us": {"mean": round(attend_us, 2), "median": round(att_us[K_steps // 2], 2),
+                      "min": round(att_us[0], 2)},
+        "retrieve_gbps": round(gbps(retrieve_bytes, retrieve_us), 1),
+        "retrieve_frac_of_hbm_peak": round(gbps(retrieve_bytes, retrieve_us) / HBM_PEAK_GBPS, 4),
+        "attend_gbps": round(gbps(attend_bytes, attend_us), 1),
+        "attend_frac_of_hbm_peak": round(gbps(attend_bytes, attend_us) / HBM_PEAK_GBPS, 4),
+        "kernel_us": {kname: (round(v, 2) if v is not None else None) for kname, v in stage_us.items()},
+        "bulk_hash_keys_ms_per_layer": round(bulk_ms, 3),
+        "bulk_hash_keys_gflops": round(2.0 * B * Hkv * N * (cfg.hidden * d + L * cfg.hidden if cfg.hidden else L * d)
+                                       / (bulk_ms * 1e-3) / 1e9, 1),
+        "setup_s": round(t_gen, 1),
+        "roofline": roofline,
+        "roofline_attend": roofline_attend,
+    }
+
+    # ------------------------------------------------------------------ the oracle on the host cores
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, layers[0], args.cpu_heads)
+
+    ctx.close()
+    print(json.dumps(result))
+
+
+def cpu_baseline(cfg, lay, n_heads):
+    """Times the CPU oracle on the retrieval of a few heads of the same workload (same seeded K
+    rows and weights as layer 0), and scales the per-head time to all heads."""
+    import torch
+    import oracle
+
+    Hkv, G, N, k = cfg.n_kv_heads, cfg.group, cfg.n_tokens, cfg.topk
+    n_heads = max(1, min(n_heads, Hkv))
+    w = lay["w"]
+    hw = w.hash_weights()
+    heads = list(range(n_heads))
+    # inputs come from the seeded generator (its device copy), never from the HIP kernels
+    hK = lay["K"][0, heads].cpu().unsqueeze(0).contiguous()          # [1, n_heads, Nmax, d]
+    hV = lay["V"][0, heads].cpu().unsqueeze(0).contiguous()
+    w1, b1, w2 = (None if t is None else t[heads].contiguous() for t in hw)
+    q = w.q[0:1, : n_heads * G].contiguous()
+    codes = torch.zeros(1, n_heads, cfg.max_tokens, cfg.words, dtype=torch.int32)
+    t0 = time.perf_counter()
+    oracle.hash_keys(hK, w1, b1, w2, cfg.code_bits, 0, N, codes)         # setup: the oracle's own codes
+    t_build = time.perf_counter() - t0
+    reps = 3
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        idx, _, _ = oracle.retrieve_topk(q, w1, b1, w2, codes, N, k)
+    t_retr = (time.perf_counter() - t0) / reps
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        oracle.sparse_decode(q, hK, hV, idx, 1.0 / math.sqrt(cfg.head_dim))
+    t_att = (time.perf_counter() - t0) / reps
+    per_q_head = t_retr / (n_heads * G)
+    return {
+        "value": round(per_q_head * cfg.batch * cfg.n_q_heads * 1e6, 1),
+        "unit": "us",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"retrieval (query hash + bit-by-bit Hamming + full sort) of {n_heads * G} of "
+                  f"{cfg.batch * cfg.n_q_heads} query heads of layer 0 at full context, mean of {reps} runs, "
+                  f"scaled by heads; key codes built by the oracle beforehand ({t_build:.1f} s, untimed)",
+        "attend_us_scaled": round(t_att / (n_heads * G) * cfg.batch * cfg.n_q_heads * 1e6, 1),
+        "hash_keys_us_per_key": round(t_build / (n_heads * N) * 1e6, 3),
+    }
+
+
+if __name__ == "__main__":
+    main()

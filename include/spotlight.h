@@ -48,14 +48,12 @@ enum {
 
 /* Kernel stages, for spotlight_profile_read. */
 enum {
-    SPOTLIGHT_STAGE_HASH_KEYS = 0,  /* hash + pack of key rows                     */
-    SPOTLIGHT_STAGE_HASH_QUERY = 1, /* hash + pack of the query vectors            */
-    SPOTLIGHT_STAGE_SCORE = 2,      /* Hamming distances + per-block histograms    */
-    SPOTLIGHT_STAGE_SCAN = 3,       /* threshold and output offsets per head       */
-    SPOTLIGHT_STAGE_SELECT = 4,     /* ordered compaction of the selected indices  */
-    SPOTLIGHT_STAGE_ATTEND = 5,     /* gather + partial softmax attention          */
-    SPOTLIGHT_STAGE_MERGE = 6,      /* merge of the partial results                */
-    SPOTLIGHT_STAGE_COUNT = 7
+    SPOTLIGHT_STAGE_HASH_KEYS = 0,  /* hash + pack of key rows                                   */
+    SPOTLIGHT_STAGE_HASH_QUERY = 1, /* hash + pack of the query vectors                          */
+    SPOTLIGHT_STAGE_SCORE = 2,      /* Hamming distances, histograms, candidate lists            */
+    SPOTLIGHT_STAGE_SELECT = 3,     /* threshold, offsets, ordered output of the selected tokens */
+    SPOTLIGHT_STAGE_ATTEND = 4,     /* gather + softmax attention (partials and their merge)     */
+    SPOTLIGHT_STAGE_COUNT = 5
 };
 
 typedef struct {
@@ -90,8 +88,8 @@ int spotlight_validate_config(const spotlight_config *cfg);
 size_t spotlight_workspace_bytes(const spotlight_config *cfg);
 
 /* Allocates the context and its device workspace on the current device.  *out is set only on
- * success.  The workspace holds the query codes, one distance per (query head, token), per-block
- * histograms, and the partial attention results. */
+ * success.  The workspace holds the query codes, per-block distance histograms and candidate
+ * lists (about one byte per (query head, token)), and the partial attention results. */
 int spotlight_create(spotlight_ctx **out, const spotlight_config *cfg);
 
 /* Waits for the stream, frees the workspace and the context.  NULL is accepted. */

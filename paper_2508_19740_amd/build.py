@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-LIB = os.path.join(HERE, "libspotlight.so")
+LIB = os.environ.get("SPOTLIGHT_LIB") or os.path.join(HERE, "libspotlight.so")
 SOURCES = ["api.hip", "hash.hip", "retrieve.hip", "attend.hip"]
 
 # -ffp-contract=off: the hash codes are defined by an exact sequence of binary32 operations, so

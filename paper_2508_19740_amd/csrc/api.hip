@@ -39,24 +39,17 @@ int make_plan(const spotlight_config* c, Plan* p)
     p->kv_dtype = c->kv_dtype;
     p->w_dtype = c->weight_dtype;
 
-    // Tokens per score/select workgroup: 4096 (256 threads x 16) unless that leaves the chip with
-    // fewer than ~1024 workgroups, then down to 1024.
-    int tpb = 4096;
-    const int64_t kv_heads = static_cast<int64_t>(p->B) * p->Hkv;
-    while (tpb > 1024 && kv_heads * ((p->Nmax + tpb - 1) / tpb) < 1024) tpb >>= 1;
-    p->tokens_per_block = tpb;
-    p->max_blocks = static_cast<int>((p->Nmax + tpb - 1) / tpb);
-    p->dist_bytes = p->L < 256 ? 1 : 2;
-    p->dist_stride = static_cast<int64_t>(align_up(static_cast<size_t>(p->Nmax), 64));
+    p->max_blocks = static_cast<int>((p->Nmax + kTokensPerBlock - 1) / kTokensPerBlock);
     p->max_splits = (p->max_topk + kAttendMinRows - 1) / kAttendMinRows;
 
     const size_t BH = static_cast<size_t>(p->B) * p->Hq;
+    const size_t bins = static_cast<size_t>(p->L) + 1;
     size_t off = 0;
     p->off_qcode = off;     off = align_up(off + BH * p->W * 4, 256);
-    p->off_dist = off;      off = align_up(off + BH * static_cast<size_t>(p->dist_stride) * p->dist_bytes, 256);
-    p->off_blockhist = off; off = align_up(off + BH * p->max_blocks * static_cast<size_t>(p->L + 1) * 4, 256);
-    p->off_blockinfo = off; off = align_up(off + BH * p->max_blocks * 8, 256);
-    p->off_headinfo = off;  off = align_up(off + BH * 8, 256);
+    p->off_gcum = off;      off = align_up(off + BH * bins * 4, 256);
+    p->off_blockcum = off;  off = align_up(off + BH * p->max_blocks * bins * 4, 256);
+    p->off_blockmeta = off; off = align_up(off + BH * p->max_blocks * 8, 256);
+    p->off_cand = off;      off = align_up(off + BH * p->max_blocks * static_cast<size_t>(kCandCap) * 4, 256);
     p->off_part_ml = off;   off = align_up(off + BH * p->max_splits * 8, 256);
     p->off_part_acc = off;  off = align_up(off + BH * p->max_splits * static_cast<size_t>(kHeadDim) * 4, 256);
     p->total_bytes = off;
@@ -139,14 +132,16 @@ int spotlight_create(spotlight_ctx** out, const spotlight_config* cfg)
     ctx->stream = static_cast<hipStream_t>(cfg->stream);
     ctx->recs = new (std::nothrow) ProfileRec[kMaxProfile];
     if (!ctx->recs) { delete ctx; return SPOTLIGHT_ERR_WORKSPACE; }
-    int dev = 0, lds = 0;
+    int dev = 0, lds = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) {
+        hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
         delete[] ctx->recs;
         delete ctx;
         return SPOTLIGHT_ERR_HIP;
     }
     ctx->max_lds = lds;
+    ctx->n_cus = cus;
     void* ws = nullptr;
     if (hipMalloc(&ws, plan.total_bytes) != hipSuccess) {
         (void)hipGetLastError();
@@ -208,6 +203,8 @@ int spotlight_hash_keys(spotlight_ctx* ctx, const void* K, const spotlight_hash_
     h.codes = codes;
     h.code_head_stride = p.Nmax * p.W;
     h.code_row0 = t0;
+    h.zero = nullptr;
+    h.zero_words = 0;
     return launch_hash(ctx, h, SPOTLIGHT_STAGE_HASH_KEYS);
 }
 
@@ -241,6 +238,8 @@ int spotlight_retrieve_topk(spotlight_ctx* ctx, const void* q, const spotlight_h
     h.codes = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_qcode);
     h.code_head_stride = p.W;
     h.code_row0 = 0;
+    h.zero = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_gcum);  // the score kernel adds into it
+    h.zero_words = p.L + 1;
     rc = launch_hash(ctx, h, SPOTLIGHT_STAGE_HASH_QUERY);
     if (rc != SPOTLIGHT_OK) return rc;
     if (out_qcode) {

@@ -6,8 +6,10 @@
 // instruction.  A wavefront first issues the loads of ALL its K rows and V rows (up to 16 KB in
 // flight per wave: the kernel is bound by random-row HBM latency x bandwidth, not arithmetic),
 // then forms the scores, a wave-local softmax in binary32, and the weighted sum of its V rows.
-// Workgroup partials (max, sum, acc[128]) go to the workspace and a small second kernel merges
-// the partials of each head with the usual max-rescaling.
+// Workgroup partials (max, sum, acc[128]) go to the workspace and a second small kernel merges the
+// partials of each head with the usual max-rescaling.  (Merging in the last workgroup to arrive
+// needs a device-wide fence per workgroup, which on this chip writes back the L2: measured 8x
+// slower than the extra launch.)
 #include "internal.h"
 
 namespace spotlight {
@@ -162,26 +164,59 @@ __global__ __launch_bounds__(kThreads) void attend_kernel(
     }
 }
 
-__global__ __launch_bounds__(kHeadDim) void merge_kernel(const float2* __restrict__ part_ml,
+// Merge of the partials of one head.  256 threads: thread (c, half) owns output column c and the
+// splits of parity `half`, folded in split order with a running maximum.  Loads are issued eight
+// splits at a time, ahead of the arithmetic that depends on them; the two halves are combined at
+// the end.
+__global__ __launch_bounds__(kThreads) void merge_kernel(const float2* __restrict__ part_ml,
                                                          const float* __restrict__ part_acc,
                                                          float* __restrict__ out, int nsplit, int max_splits)
 {
-    const int c = threadIdx.x;
+    constexpr int NB = 8;
+    __shared__ float s_m[kHeadDim], s_a[kHeadDim], s_l[kHeadDim];
+    const int tid = threadIdx.x;
     const int64_t bh = blockIdx.x;
     const float2* ml = part_ml + bh * max_splits;
     const float* pa = part_acc + bh * max_splits * kHeadDim;
-    float M = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, ml[s].x);
-    float a = 0.0f, l = 0.0f;
-    if (M > -INFINITY) {
-        for (int s = 0; s < nsplit; ++s) {
-            const float2 v = ml[s];
-            const float f = v.x > -INFINITY ? __expf(v.x - M) : 0.0f;
-            a = __builtin_fmaf(f, pa[static_cast<int64_t>(s) * kHeadDim + c], a);
-            l = __builtin_fmaf(f, v.y, l);
+    const int c = tid & (kHeadDim - 1), half = tid >> 7;
+    float m = -INFINITY, a = 0.0f, l = 0.0f;
+    for (int s0 = half; s0 < nsplit; s0 += 2 * NB) {
+        float2 v[NB];
+        float av[NB];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int sp = s0 + 2 * i;
+            const int spc = sp < nsplit ? sp : s0;         // in-bounds stand-in, masked below
+            v[i] = ml[spc];
+            av[i] = pa[static_cast<int64_t>(spc) * kHeadDim + c];
+            if (sp >= nsplit) v[i].x = -INFINITY;
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            if (v[i].x > -INFINITY) {
+                const float mn = fmaxf(m, v[i].x);
+                const float fo = __expf(m - mn), fn = __expf(v[i].x - mn);  // exp(-inf) = 0 on the first split
+                a = __builtin_fmaf(a, fo, fn * av[i]);
+                l = __builtin_fmaf(l, fo, fn * v[i].y);
+                m = mn;
+            }
         }
     }
-    out[bh * kHeadDim + c] = l > 0.0f ? a / l : 0.0f;
+    if (half == 1) { s_m[c] = m; s_a[c] = a; s_l[c] = l; }
+    __syncthreads();
+    if (half == 0) {
+        const float m1 = s_m[c];
+        const float mn = fmaxf(m, m1);
+        float res = 0.0f;
+        if (mn > -INFINITY) {
+            const float f0 = m > -INFINITY ? __expf(m - mn) : 0.0f;
+            const float f1 = m1 > -INFINITY ? __expf(m1 - mn) : 0.0f;
+            const float at = __builtin_fmaf(a, f0, f1 * s_a[c]);
+            const float lt = __builtin_fmaf(l, f0, f1 * s_l[c]);
+            res = lt > 0.0f ? at / lt : 0.0f;
+        }
+        out[bh * kHeadDim + c] = res;
+    }
 }
 
 template <typename T, int RB>
@@ -207,22 +242,15 @@ int launch_t(spotlight_ctx* ctx, const void* q, const void* K, const void* V, co
     int RB = 128;
     while (RB > kAttendMinRows && heads * ((k + RB - 1) / RB) < 1024) RB >>= 1;
     const int nsplit = (k + RB - 1) / RB;
-    {
-        StageTimer timer(ctx, SPOTLIGHT_STAGE_ATTEND);
-        if (RB == 128) launch_rb<T, 128>(ctx, q, K, V, idx, k, scale, nsplit);
-        else if (RB == 64) launch_rb<T, 64>(ctx, q, K, V, idx, k, scale, nsplit);
-        else launch_rb<T, 32>(ctx, q, K, V, idx, k, scale, nsplit);
-        if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
-    }
-    {
-        StageTimer timer(ctx, SPOTLIGHT_STAGE_MERGE);
-        hipLaunchKernelGGL(merge_kernel, dim3(static_cast<unsigned>(heads)), dim3(kHeadDim), 0, ctx->stream,
-                           reinterpret_cast<const float2*>(ctx->workspace + p.off_part_ml),
-                           reinterpret_cast<const float*>(ctx->workspace + p.off_part_acc), out, nsplit,
-                           p.max_splits);
-        if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
-    }
-    return SPOTLIGHT_OK;
+    StageTimer timer(ctx, SPOTLIGHT_STAGE_ATTEND);  // both kernels count as the attend stage
+    if (RB == 128) launch_rb<T, 128>(ctx, q, K, V, idx, k, scale, nsplit);
+    else if (RB == 64) launch_rb<T, 64>(ctx, q, K, V, idx, k, scale, nsplit);
+    else launch_rb<T, 32>(ctx, q, K, V, idx, k, scale, nsplit);
+    if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
+    hipLaunchKernelGGL(merge_kernel, dim3(static_cast<unsigned>(heads)), dim3(kThreads), 0, ctx->stream,
+                       reinterpret_cast<const float2*>(ctx->workspace + p.off_part_ml),
+                       reinterpret_cast<const float*>(ctx->workspace + p.off_part_acc), out, nsplit, p.max_splits);
+    return hip_rc(hipGetLastError());
 }
 
 }  // namespace

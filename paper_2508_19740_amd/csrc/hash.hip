@@ -37,6 +37,27 @@ __device__ __forceinline__ void load8(const bf16_raw* p, float (&o)[8])
     o[4] = __uint_as_float(u.z << 16); o[5] = __uint_as_float(u.z & 0xffff0000u);
     o[6] = __uint_as_float(u.w << 16); o[7] = __uint_as_float(u.w & 0xffff0000u);
 }
+// 8 consecutive weights kept in their stored form (converted when used)
+template <typename WT> struct Raw8;
+template <> struct Raw8<float> { float4 a, b; };
+template <> struct Raw8<bf16_raw> { uint4 u; };
+__device__ __forceinline__ void load_raw(const float* p, Raw8<float>& r)
+{
+    r.a = reinterpret_cast<const float4*>(p)[0];
+    r.b = reinterpret_cast<const float4*>(p)[1];
+}
+__device__ __forceinline__ void load_raw(const bf16_raw* p, Raw8<bf16_raw>& r) { r.u = *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void expand(const Raw8<float>& r, float (&o)[8])
+{
+    o[0] = r.a.x; o[1] = r.a.y; o[2] = r.a.z; o[3] = r.a.w; o[4] = r.b.x; o[5] = r.b.y; o[6] = r.b.z; o[7] = r.b.w;
+}
+__device__ __forceinline__ void expand(const Raw8<bf16_raw>& r, float (&o)[8])
+{
+    o[0] = __uint_as_float(r.u.x << 16); o[1] = __uint_as_float(r.u.x & 0xffff0000u);
+    o[2] = __uint_as_float(r.u.y << 16); o[3] = __uint_as_float(r.u.y & 0xffff0000u);
+    o[4] = __uint_as_float(r.u.z << 16); o[5] = __uint_as_float(r.u.z & 0xffff0000u);
+    o[6] = __uint_as_float(r.u.w << 16); o[7] = __uint_as_float(r.u.w & 0xffff0000u);
+}
 __device__ __forceinline__ float load1(const float* p) { return *p; }
 __device__ __forceinline__ float load1(const bf16_raw* p) { return bf16_bits_to_f32(p->v); }
 
@@ -92,12 +113,50 @@ struct HashArgs {
     int hidden, L, W;
     uint32_t* codes;
     int64_t code_head_stride, code_row0;
+    uint32_t* zero;
+    int zero_words;
 };
+
+// acc[t] += sum over n8*8 consecutive weights of `row` times act[(i)*stride + t], in increasing i,
+// one fused multiply-add per term.  PF groups of 8 weights are fetched ahead of their use.
+template <typename WT, int TK, int PF>
+__device__ __forceinline__ void dot_rows(const WT* __restrict__ row, int n8, const float* act, int stride,
+                                         float (&acc)[TK])
+{
+    int g = 0;
+    for (; g + PF <= n8; g += PF) {
+        float wv[PF][8];
+#pragma unroll
+        for (int p = 0; p < PF; ++p) load8(row + (g + p) * 8, wv[p]);
+#pragma unroll
+        for (int p = 0; p < PF; ++p)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                float xr[TK];
+                lds_tile<TK>(act + ((g + p) * 8 + j) * stride, xr);
+#pragma unroll
+                for (int t = 0; t < TK; ++t) acc[t] = __builtin_fmaf(wv[p][j], xr[t], acc[t]);
+            }
+    }
+    for (; g < n8; ++g) {
+        float wv[8];
+        load8(row + g * 8, wv);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float xr[TK];
+            lds_tile<TK>(act + (g * 8 + j) * stride, xr);
+#pragma unroll
+            for (int t = 0; t < TK; ++t) acc[t] = __builtin_fmaf(wv[j], xr[t], acc[t]);
+        }
+    }
+}
 
 // LDS: xs [128][TK] floats, then hs [hidden][TK] floats (hidden > 0 only).
 template <typename XT, typename WT, int TK, int KSPLIT>
 __global__ __launch_bounds__(kThreads) void hash_kernel(HashArgs a)
 {
+    constexpr int TK2 = TK / KSPLIT;
+    constexpr int PF = TK == 1 ? 16 : (TK <= 8 ? 2 : 1);  // weight groups fetched ahead
     extern __shared__ __align__(16) float lds[];
     float* xs = lds;
     float* hs = lds + kHeadDim * TK;
@@ -107,6 +166,8 @@ __global__ __launch_bounds__(kThreads) void hash_kernel(HashArgs a)
     const int64_t r0 = static_cast<int64_t>(blockIdx.x) * TK;
     const int rows = static_cast<int>(min(static_cast<int64_t>(TK), a.n_rows - r0));
     const int whead = (xhead % a.heads_per_batch) / a.group;
+    if (a.zero && blockIdx.x == 0)
+        for (int i = tid; i < a.zero_words; i += kThreads) a.zero[static_cast<int64_t>(xhead) * a.zero_words + i] = 0u;
 
     // ---- stage the x tile, transposed to [k][t], rows past the end as zeros
     const XT* xbase = static_cast<const XT*>(a.x) + xhead * a.x_head_stride + (a.x_row0 + r0) * kHeadDim;
@@ -131,18 +192,7 @@ __global__ __launch_bounds__(kThreads) void hash_kernel(HashArgs a)
             const float bias = load1(b1 + i);
 #pragma unroll
             for (int t = 0; t < TK; ++t) acc[t] = bias;
-            const WT* row = w1 + static_cast<int64_t>(i) * kHeadDim;
-            for (int k8 = 0; k8 < kHeadDim / 8; ++k8) {
-                float wv[8];
-                load8(row + k8 * 8, wv);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    float xr[TK];
-                    lds_tile<TK>(xs + (k8 * 8 + j) * TK, xr);
-#pragma unroll
-                    for (int t = 0; t < TK; ++t) acc[t] = __builtin_fmaf(wv[j], xr[t], acc[t]);
-                }
-            }
+            dot_rows<WT, TK, PF>(w1 + static_cast<int64_t>(i) * kHeadDim, kHeadDim / 8, xs, TK, acc);
 #pragma unroll
             for (int t = 0; t < TK; ++t) hs[i * TK + t] = silu(acc[t]);
         }
@@ -153,7 +203,6 @@ __global__ __launch_bounds__(kThreads) void hash_kernel(HashArgs a)
     }
 
     // ---- phase 2: outputs, sign, ballot-pack
-    constexpr int TK2 = TK / KSPLIT;
     const int lane = tid & 63, wave = tid >> 6;
     const int npairs = (a.W + 1) / 2;
     uint32_t* cbase = a.codes + xhead * a.code_head_stride + (a.code_row0 + r0) * a.W;
@@ -166,17 +215,7 @@ __global__ __launch_bounds__(kThreads) void hash_kernel(HashArgs a)
         float y[TK2];
 #pragma unroll
         for (int t = 0; t < TK2; ++t) y[t] = 0.0f;
-        for (int i8 = 0; i8 < act_dim / 8; ++i8) {
-            float wv[8];
-            load8(row + i8 * 8, wv);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                float hr[TK2];
-                lds_tile<TK2>(act + (i8 * 8 + j) * TK + ks * TK2, hr);
-#pragma unroll
-                for (int t = 0; t < TK2; ++t) y[t] = __builtin_fmaf(wv[j], hr[t], y[t]);
-            }
-        }
+        dot_rows<WT, TK2, PF>(row, act_dim / 8, act + ks * TK2, TK, y);
 #pragma unroll
         for (int t = 0; t < TK2; ++t) {
             const unsigned long long m = __ballot(live && (y[t] > 0.0f));
@@ -187,6 +226,124 @@ __global__ __launch_bounds__(kThreads) void hash_kernel(HashArgs a)
             }
         }
     }
+}
+
+// One vector per workgroup (the query of a head, or the key appended by a decode step), for hidden
+// widths that are multiples of 128 (or the linear hash).  Latency matters here, not throughput: x
+// is read through uniform addresses, and every thread fetches its whole W1 row and the first 256
+// weights of its W2 row (kept in their stored form) before any arithmetic, so a hidden width of
+// 256 costs one round trip to memory.  The only LDS traffic is the broadcast of the hidden
+// activations.  Same arithmetic, same order as the tiled kernel.
+template <typename XT, typename WT>
+__global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashArgs a)
+{
+    extern __shared__ __align__(16) float act[];  // hidden activations, or x itself for the linear hash
+    constexpr int G16 = kHeadDim / 8;             // groups of 8 in a run of 128 weights
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int xhead = blockIdx.x;
+    const int whead = (xhead % a.heads_per_batch) / a.group;
+    const XT* x = static_cast<const XT*>(a.x) + xhead * a.x_head_stride + a.x_row0 * kHeadDim;
+    const int act_dim = a.hidden > 0 ? a.hidden : kHeadDim;   // multiple of 128
+    const int n16 = act_dim / kHeadDim;                        // runs of 128 weights per output row
+    const WT* wout = a.hidden > 0 ? static_cast<const WT*>(a.w2) + static_cast<int64_t>(whead) * a.L * a.hidden
+                                  : static_cast<const WT*>(a.w1) + static_cast<int64_t>(whead) * a.L * kHeadDim;
+    const int npairs = (a.W + 1) / 2;
+
+    // fetch the first two runs of this thread's first output row
+    const int word0 = 2 * wave + (lane >> 5);
+    const bool live0 = wave < npairs && word0 < a.W;
+    const int o0 = live0 ? (31 - (lane & 31)) * a.W + word0 : 0;
+    Raw8<WT> ra[G16], rb[G16];
+    {
+        const WT* row = wout + static_cast<int64_t>(o0) * act_dim;
+#pragma unroll
+        for (int g = 0; g < G16; ++g) load_raw(row + g * 8, ra[g]);
+        if (n16 > 1) {
+#pragma unroll
+            for (int g = 0; g < G16; ++g) load_raw(row + kHeadDim + g * 8, rb[g]);
+        }
+    }
+
+    if (a.hidden > 0) {
+        const WT* w1 = static_cast<const WT*>(a.w1) + static_cast<int64_t>(whead) * a.hidden * kHeadDim;
+        const WT* b1 = static_cast<const WT*>(a.b1) + static_cast<int64_t>(whead) * a.hidden;
+        for (int i = tid; i < a.hidden; i += kThreads) {
+            Raw8<WT> w1r[G16];
+#pragma unroll
+            for (int g = 0; g < G16; ++g) load_raw(w1 + static_cast<int64_t>(i) * kHeadDim + g * 8, w1r[g]);
+            float acc = load1(b1 + i);
+#pragma unroll
+            for (int g = 0; g < G16; ++g) {
+                float xv[8], wv[8];
+                load8(x + g * 8, xv);
+                expand(w1r[g], wv);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc = __builtin_fmaf(wv[j], xv[j], acc);
+            }
+            act[i] = silu(acc);
+        }
+    } else {
+        for (int e = tid; e < G16; e += kThreads) {
+            float xv[8];
+            load8(x + e * 8, xv);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) act[e * 8 + j] = xv[j];
+        }
+    }
+    __syncthreads();
+
+    auto run128 = [&](const Raw8<WT> (&r)[G16], const float* h, float y) {
+#pragma unroll
+        for (int g = 0; g < G16; ++g) {
+            float wv[8];
+            expand(r[g], wv);
+            const float4 h0 = reinterpret_cast<const float4*>(h + g * 8)[0];
+            const float4 h1 = reinterpret_cast<const float4*>(h + g * 8)[1];
+            y = __builtin_fmaf(wv[0], h0.x, y); y = __builtin_fmaf(wv[1], h0.y, y);
+            y = __builtin_fmaf(wv[2], h0.z, y); y = __builtin_fmaf(wv[3], h0.w, y);
+            y = __builtin_fmaf(wv[4], h1.x, y); y = __builtin_fmaf(wv[5], h1.y, y);
+            y = __builtin_fmaf(wv[6], h1.z, y); y = __builtin_fmaf(wv[7], h1.w, y);
+        }
+        return y;
+    };
+
+    uint32_t* cbase = a.codes + xhead * a.code_head_stride + a.code_row0 * a.W;
+    for (int pair = wave; pair < npairs; pair += kThreads / 64) {
+        const int word = 2 * pair + (lane >> 5);
+        const bool live = word < a.W;
+        const int o = live ? (31 - (lane & 31)) * a.W + word : 0;
+        const WT* row = wout + static_cast<int64_t>(o) * act_dim;
+        float y = 0.0f;
+        for (int r0 = 0; r0 < n16; r0 += 2) {
+            if (pair != wave || r0 != 0) {   // the first two runs of the first row are already here
+#pragma unroll
+                for (int g = 0; g < G16; ++g) load_raw(row + r0 * kHeadDim + g * 8, ra[g]);
+                if (r0 + 1 < n16) {
+#pragma unroll
+                    for (int g = 0; g < G16; ++g) load_raw(row + (r0 + 1) * kHeadDim + g * 8, rb[g]);
+                }
+            }
+            y = run128(ra, act + r0 * kHeadDim, y);
+            if (r0 + 1 < n16) y = run128(rb, act + (r0 + 1) * kHeadDim, y);
+        }
+        const unsigned long long m = __ballot(live && (y > 0.0f));
+        if (lane == 0) {
+            cbase[2 * pair] = static_cast<uint32_t>(m);
+            if (2 * pair + 1 < a.W) cbase[2 * pair + 1] = static_cast<uint32_t>(m >> 32);
+        }
+    }
+    if (a.zero)
+        for (int i = tid; i < a.zero_words; i += kThreads) a.zero[static_cast<int64_t>(xhead) * a.zero_words + i] = 0u;
+}
+
+template <typename XT, typename WT>
+int run_vec(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
+{
+    const size_t lds = sizeof(float) * (a.hidden > 0 ? a.hidden : kHeadDim);
+    StageTimer timer(ctx, stage);
+    hipLaunchKernelGGL((hash_vec_kernel<XT, WT>), dim3(static_cast<unsigned>(n_xheads)), dim3(kThreads), lds, ctx->stream, a);
+    return hip_rc(hipGetLastError());
 }
 
 inline size_t lds_bytes(int tk, int hidden) { return sizeof(float) * tk * (kHeadDim + hidden); }
@@ -226,6 +383,8 @@ template <typename XT, typename WT>
 int run_tk(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
 {
     const size_t cap = static_cast<size_t>(ctx->max_lds);
+    // a single vector per head, hidden width a multiple of 128: the latency-oriented kernel
+    if (a.n_rows == 1 && a.hidden % kHeadDim == 0) return run_vec<XT, WT>(ctx, a, n_xheads, stage);
     if (a.n_rows >= 32 && lds_bytes(32, a.hidden) <= cap) return run_ks<XT, WT, 32>(ctx, a, n_xheads, stage);
     if (a.n_rows >= 4 && lds_bytes(8, a.hidden) <= cap) return run_ks<XT, WT, 8>(ctx, a, n_xheads, stage);
     return run_ks<XT, WT, 1>(ctx, a, n_xheads, stage);
@@ -255,6 +414,8 @@ int launch_hash(spotlight_ctx* ctx, const HashLaunch& h, int stage)
     a.codes = h.codes;
     a.code_head_stride = h.code_head_stride;
     a.code_row0 = h.code_row0;
+    a.zero = h.zero;
+    a.zero_words = h.zero_words;
     const bool xb = h.x_dtype == SPOTLIGHT_BF16, wb = h.w_dtype == SPOTLIGHT_BF16;
     if (xb && wb) return run_tk<bf16_raw, bf16_raw>(ctx, a, h.n_xheads, stage);
     if (xb && !wb) return run_tk<bf16_raw, float>(ctx, a, h.n_xheads, stage);

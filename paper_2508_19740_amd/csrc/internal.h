@@ -12,6 +12,8 @@ constexpr int kHeadDim = 128;
 constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts of 64 lanes per workgroup
 constexpr int kMaxGroup = 8;        // query heads per key-value head
 constexpr int kAttendMinRows = 32;  // smallest number of gathered rows one workgroup takes
+constexpr int kTokensPerBlock = 4096;  // tokens one score / select workgroup covers (16 per thread)
+constexpr int kCandCap = 1024;      // candidate-list entries per (query head, token block)
 constexpr int kMaxProfile = 8192;
 
 // Geometry derived once from the configuration.
@@ -20,13 +22,16 @@ struct Plan {
     int64_t Nmax;
     int max_topk;
     int kv_dtype, w_dtype;
-    int tokens_per_block;  // tokens one score / select workgroup covers
-    int max_blocks;        // ceil(Nmax / tokens_per_block)
-    int dist_bytes;        // 1 if L < 256 else 2
-    int64_t dist_stride;   // distances per query head in the workspace (Nmax rounded up to 64)
+    int max_blocks;        // ceil(Nmax / kTokensPerBlock)
     int max_splits;        // ceil(max_topk / kAttendMinRows)
     // workspace offsets in bytes
-    size_t off_qcode, off_dist, off_blockhist, off_blockinfo, off_headinfo, off_part_ml, off_part_acc;
+    size_t off_qcode;      // [B*Hq][W] query codes
+    size_t off_gcum;       // [B*Hq][L+1] cumulative distance histogram of the head
+    size_t off_blockcum;   // [B*Hq][max_blocks][L+1] cumulative histogram of each token block
+    size_t off_blockmeta;  // [B*Hq][max_blocks] {candidate bound, four sub-list lengths}
+    size_t off_cand;       // [B*Hq][max_blocks][4][kCandCap/4] candidates (distance << 16 | block offset)
+    size_t off_part_ml;    // [B*Hq][max_splits] {max, sum} of each attention split
+    size_t off_part_acc;   // [B*Hq][max_splits][128] weighted value sums of each split
     size_t total_bytes;
 };
 
@@ -45,6 +50,7 @@ struct spotlight_ctx {
     hipStream_t stream;
     char* workspace;
     int max_lds;                     // bytes of LDS one workgroup may use on this device
+    int n_cus;                       // compute units of this device
     // profiling
     int profiling;
     int n_rec;                       // records in use since the last read
@@ -81,6 +87,8 @@ struct HashLaunch {
     uint32_t* codes;
     int64_t code_head_stride; // words between consecutive x-heads
     int64_t code_row0;
+    uint32_t* zero;           // if set: zero[xhead * zero_words ...) is cleared by the head's first tile
+    int zero_words;
 };
 int launch_hash(spotlight_ctx* ctx, const HashLaunch& a, int stage);
 

@@ -1,381 +1,526 @@
 // Hamming scoring and per-head top-k (paper Sec. 3.2, Eq. 3 and the top-k that follows it).
 //
-// Distances are integers in 0..L, so the k nearest tokens are found by counting, not sorting:
+// Distances are integers in 0..L, so the k nearest tokens are found by counting, not sorting, and
+// the key codes are streamed from HBM exactly once:
 //
-//   score   one workgroup per (batch, key-value head, block of tokens) streams the packed key
-//           codes once, XORs them with the G query codes of the group, popcounts, stores one small
-//           integer distance per (query head, token) and counts the distances of its block in an
-//           LDS histogram (replicated over lanes to keep same-address atomics apart);
-//   scan    one workgroup per query head adds the block histograms, finds the threshold T with
-//           count(d < T) < k <= count(d <= T) and the number r = k - count(d < T) of tokens to take
-//           from the tie bucket d == T, and turns the per-block counts into an output offset and a
-//           tie quota per block (prefix sums over blocks, in token order);
-//   select  one workgroup per (query head, block) re-reads its distances (one or two bytes per
-//           token, not the codes), keeps d < T plus the first `quota` tokens with d == T, and writes
-//           the kept token indices at offset + rank.
+//   score   one workgroup per (batch, key-value head, block of 4096 tokens) reads the packed key
+//           codes of its block, XORs them with the G query codes of the group and popcounts; the
+//           16 distances of each thread stay in registers.  The block counts them in an LDS
+//           histogram (replicated over lanes so that same-address atomics stay apart), turns it
+//           into a cumulative histogram, stores that per block and adds it to the cumulative
+//           histogram of the head (integer atomics).  It then keeps a short list of CANDIDATES:
+//           the tokens up to a block-local distance bound chosen so that about twice the block's
+//           fair share of k qualifies (one sub-list per wavefront).  Nothing else is written per
+//           token.  Workgroups are persistent and fetch the next keys before finishing a block.
+//   select  one workgroup per (query head, block).  The head's cumulative histogram gives the
+//           exact threshold T with count(d < T) < k <= count(d <= T) and r = k - count(d < T),
+//           the number of tokens to take from the tie bucket d == T.  The cumulative histograms of
+//           the preceding blocks give this block's output offset and its share of the tie bucket
+//           (ties go to the lower token index).  If T is within the block's candidate bound, the
+//           block's tokens with d <= T are all in its list; otherwise (rare) the block recomputes
+//           its distances from the codes.  Selected tokens are marked in an LDS bitmap and written
+//           out in increasing token order.
 //
 // The result is exactly the first k tokens in (distance, token index) order, listed by increasing
-// token index, with no atomics on the output path: identical bits on every run.
+// token index, with integer arithmetic only: identical bits on every run.
 #include "internal.h"
 
 namespace spotlight {
 namespace {
 
-constexpr int kMaxBins = 513;  // L <= 512
+constexpr int kTPB = kTokensPerBlock;       // tokens per workgroup
+constexpr int kKPT = kTPB / kThreads;       // keys per thread (16)
+
+constexpr int kWaveCap = kCandCap / (kThreads / 64);  // entries of one wavefront's candidate sub-list (256)
+constexpr int kWaveFull = 255;              // count value meaning "this sub-list overflowed"
+
+// Per (query head, token block): the block's candidate bound and its four sub-list lengths.
+struct BlockMeta {
+    uint32_t bound;
+    uint8_t count[kThreads / 64];
+};
+static_assert(sizeof(BlockMeta) == 8, "workspace layout");
 
 __device__ __forceinline__ int popc(uint32_t x) { return __builtin_popcount(x); }
 
-// ------------------------------------------------------------------------------------ score
-// LPK lanes share one key (LPK * 4 words per key) when W is a multiple of 4; otherwise one lane
-// reads the W words of its key one by one (WORDS_GENERIC).
-template <int W, int G, typename DistT, int R>
-__global__ __launch_bounds__(kThreads) void score_kernel(
-    const uint32_t* __restrict__ codes, const uint32_t* __restrict__ qcode, DistT* __restrict__ dist,
-    uint32_t* __restrict__ blockhist, int64_t n_tokens, int64_t Nmax, int64_t dist_stride, int Hkv,
-    int tokens_per_block, int max_blocks)
+// One key (W words) at base + lane_off bytes; base is uniform over the wavefront, so the address is
+// a scalar base plus a 32-bit lane offset.  Codes are read once: non-temporal loads.
+template <int W>
+__device__ __forceinline__ void load_key(const char* __restrict__ base, uint32_t lane_off, uint32_t (&kw)[W])
 {
-    constexpr int L = W * 32;
-    constexpr int BINS = L + 1;
-    __shared__ uint32_t hist[G * BINS * R];
-
-    const int tid = threadIdx.x;
-    const int bk = blockIdx.y;               // b * Hkv + hk
-    const int blk = blockIdx.x;
-    const int Hq = Hkv * G;
-    const int b = bk / Hkv, hk = bk % Hkv;
-    const int64_t bh0 = static_cast<int64_t>(b) * Hq + hk * G;  // first query head of the group
-
-    for (int i = tid; i < G * BINS * R; i += kThreads) hist[i] = 0;
-
-    // query codes of the group: uniform over the workgroup
-    uint32_t qc[G][W];
+    if constexpr (W % 4 == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int w = 0; w < W; ++w) qc[g][w] = qcode[(bh0 + g) * W + w];
-    __syncthreads();
-
-    const int64_t t_begin = static_cast<int64_t>(blk) * tokens_per_block;
-    const int64_t t_end = min(n_tokens, t_begin + tokens_per_block);
-    const uint32_t* cbase = codes + static_cast<int64_t>(bk) * Nmax * W;
-    const int rep = tid & (R - 1);
-
-    constexpr int U = 4;  // keys in flight per lane
-    for (int64_t t0 = t_begin + tid; t0 < t_end; t0 += U * kThreads) {
-        uint32_t kw[U][W];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t t = t0 + u * kThreads;
-            if (t < t_end) {
-                if constexpr (W % 4 == 0) {
-#pragma unroll
-                    for (int w4 = 0; w4 < W / 4; ++w4) {
-                        const uint4 v = *reinterpret_cast<const uint4*>(cbase + t * W + w4 * 4);
-                        kw[u][w4 * 4 + 0] = v.x; kw[u][w4 * 4 + 1] = v.y;
-                        kw[u][w4 * 4 + 2] = v.z; kw[u][w4 * 4 + 3] = v.w;
-                    }
-                } else {
-#pragma unroll
-                    for (int w = 0; w < W; ++w) kw[u][w] = cbase[t * W + w];
-                }
-            }
+        for (int w4 = 0; w4 < W / 4; ++w4) {
+            const uint4* src = reinterpret_cast<const uint4*>(base + lane_off + w4 * 16);
+            kw[w4 * 4 + 0] = __builtin_nontemporal_load(&src->x);
+            kw[w4 * 4 + 1] = __builtin_nontemporal_load(&src->y);
+            kw[w4 * 4 + 2] = __builtin_nontemporal_load(&src->z);
+            kw[w4 * 4 + 3] = __builtin_nontemporal_load(&src->w);
         }
+    } else {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(base + lane_off);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t t = t0 + u * kThreads;
-            if (t < t_end) {
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    int d = 0;
-#pragma unroll
-                    for (int w = 0; w < W; ++w) d += popc(kw[u][w] ^ qc[g][w]);
-                    dist[(bh0 + g) * dist_stride + t] = static_cast<DistT>(d);
-                    atomicAdd(&hist[(g * BINS + d) * R + rep], 1u);
-                }
-            }
-        }
-    }
-    __syncthreads();
-
-    // fold the replicas and publish this block's histogram
-    for (int i = tid; i < G * BINS; i += kThreads) {
-        uint32_t s = 0;
-#pragma unroll
-        for (int r = 0; r < R; ++r) s += hist[i * R + r];
-        const int g = i / BINS, bin = i % BINS;
-        blockhist[((bh0 + g) * max_blocks + blk) * BINS + bin] = s;
+        for (int w = 0; w < W; ++w) kw[w] = __builtin_nontemporal_load(src + w);
     }
 }
 
-// ------------------------------------------------------------------------------------ scan
-// blockinfo[bh][blk] = {output offset of the block, tie quota of the block}; headinfo[bh] = {T, r}.
-__global__ __launch_bounds__(kThreads) void scan_kernel(
-    const uint32_t* __restrict__ blockhist, uint2* __restrict__ blockinfo, uint2* __restrict__ headinfo,
-    int bins, int nblk, int max_blocks, int k)
+// ------------------------------------------------------------------------------------ score
+struct ScoreArgs {
+    const uint32_t* codes;
+    const uint32_t* qcode;
+    uint32_t* gcum;
+    uint32_t* blockcum;
+    BlockMeta* blockmeta;
+    uint32_t* cand;
+    int64_t n_tokens, Nmax;
+    int Hkv, nblk, max_blocks, k, total_tasks, tasks_per_group;
+};
+
+// Persistent workgroups.  A task is one (batch * kv head, token block); a workgroup takes
+// tasks_per_group CONSECUTIVE tasks, which mostly belong to one head, and keeps that head's
+// cumulative histogram in LDS across them, so the (slow, device-wide) atomics into the head's
+// global histogram happen once per run of tasks instead of once per block.
+template <int W, int G, int R>
+__global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
 {
-    __shared__ uint32_t ghist[kMaxBins];
-    __shared__ uint32_t s_T, s_r;
-    __shared__ uint32_t wave_lt[kThreads / 64], wave_eq[kThreads / 64];
-    __shared__ uint32_t carry_lt, carry_eq;
+    constexpr int L = W * 32;
+    constexpr int BINS = L + 1;
+    constexpr int CH = (BINS + 63) / 64;   // bins per lane in the scan
+    constexpr int KB = W <= 4 ? 4 : (W <= 8 ? 2 : 1);  // keys in flight per lane
+    __shared__ uint32_t hist[G * BINS * R];
+    __shared__ uint32_t cum[G * BINS];     // this block's histogram, then its cumulative form
+    __shared__ uint32_t gacc[G * BINS];    // cumulative histogram summed over this run of tasks
+    __shared__ uint32_t s_thi[G];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t bh = blockIdx.x;
-    const uint32_t* bhist = blockhist + bh * max_blocks * bins;
+    const int rep = tid & (R - 1);
+    const int Hq = a.Hkv * G;
+    const uint32_t lane_off = static_cast<uint32_t>(tid) * (W * 4);
 
-    for (int bin = tid; bin < bins; bin += kThreads) {
-        uint32_t s = 0;
-        for (int blk = 0; blk < nblk; ++blk) s += bhist[static_cast<int64_t>(blk) * bins + bin];
-        ghist[bin] = s;
-    }
-    if (tid == 0) { carry_lt = 0; carry_eq = 0; }
+    for (int i = tid; i < G * BINS * R; i += kThreads) hist[i] = 0;
+    for (int i = tid; i < G * BINS; i += kThreads) gacc[i] = 0;
     __syncthreads();
-    if (tid == 0) {
-        uint32_t below = 0;
-        int T = 0;
-        for (; T < bins - 1; ++T) {
-            if (below + ghist[T] >= static_cast<uint32_t>(k)) break;
-            below += ghist[T];
-        }
-        s_T = T;
-        s_r = static_cast<uint32_t>(k) - below;  // 1 <= r <= ghist[T]
-        headinfo[bh] = make_uint2(static_cast<uint32_t>(T), s_r);
-    }
-    __syncthreads();
-    const int T = s_T;
-    const uint32_t r = s_r;
 
-    // blocks in chunks of 256, running prefix over (lt, eq) in block order
-    for (int base = 0; base < nblk; base += kThreads) {
-        const int blk = base + tid;
-        uint32_t lt = 0, eq = 0;
-        if (blk < nblk) {
-            const uint32_t* h = bhist + static_cast<int64_t>(blk) * bins;
-            for (int bin = 0; bin < T; ++bin) lt += h[bin];
-            eq = h[T];
-        }
-        // inclusive scan inside the wave
-        uint32_t slt = lt, seq = eq;
+    const int task0 = blockIdx.x * a.tasks_per_group;
+    const int task1 = min(a.total_tasks, task0 + a.tasks_per_group);
+    for (int task = task0; task < task1; ++task) {
+        const int bk = task / a.nblk, blk = task % a.nblk;
+        const int b = bk / a.Hkv, hk = bk % a.Hkv;
+        const int64_t bh0 = static_cast<int64_t>(b) * Hq + hk * G;  // first query head of the group
+        const int64_t t_begin = static_cast<int64_t>(blk) * kTPB;
+        const int n_blk = static_cast<int>(min(static_cast<int64_t>(kTPB), a.n_tokens - t_begin));
+        const char* base = reinterpret_cast<const char*>(a.codes + (static_cast<int64_t>(bk) * a.Nmax + t_begin) * W);
+
+        uint32_t qc[G][W];  // query codes of the group: uniform over the workgroup
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t a = __shfl_up(slt, off), c = __shfl_up(seq, off);
-            if (lane >= off) { slt += a; seq += c; }
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int w = 0; w < W; ++w) qc[g][w] = a.qcode[(bh0 + g) * W + w];
+
+        // distances of this thread's 16 keys, two per register; key slot i sits at block offset i*256 + tid
+        uint32_t dv[G][kKPT / 2];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int i = 0; i < kKPT / 2; ++i) dv[g][i] = 0xffffffffu;
+
+#pragma unroll
+        for (int bt = 0; bt < kKPT / KB; ++bt) {
+            uint32_t kw[KB][W];
+#pragma unroll
+            for (int u = 0; u < KB; ++u) {
+                const int i = bt * KB + u;
+                if (i * kThreads + tid < n_blk) load_key<W>(base + static_cast<size_t>(i) * (kThreads * W * 4), lane_off, kw[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < KB; ++u) {
+                const int i = bt * KB + u;
+                if (i * kThreads + tid < n_blk) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        uint32_t d = 0;
+#pragma unroll
+                        for (int w = 0; w < W; ++w) d += popc(kw[u][w] ^ qc[g][w]);
+                        atomicAdd(&hist[(g * BINS + d) * R + rep], 1u);
+                        if (i & 1) dv[g][i >> 1] = (dv[g][i >> 1] & 0x0000ffffu) | (d << 16);
+                        else dv[g][i >> 1] = (dv[g][i >> 1] & 0xffff0000u) | d;
+                    }
+                }
+            }
         }
-        if (lane == 63) { wave_lt[wave] = slt; wave_eq[wave] = seq; }
         __syncthreads();
-        uint32_t plt = carry_lt, peq = carry_eq;
-        for (int w = 0; w < wave; ++w) { plt += wave_lt[w]; peq += wave_eq[w]; }
-        const uint32_t lt_before = plt + slt - lt;   // exclusive prefixes in block order
-        const uint32_t eq_before = peq + seq - eq;
-        if (blk < nblk) {
-            const uint32_t taken_before = eq_before < r ? eq_before : r;
-            const uint32_t quota = r > eq_before ? min(r - eq_before, eq) : 0u;
-            blockinfo[bh * max_blocks + blk] = make_uint2(lt_before + taken_before, quota);
+
+        // fold the replicas (rotated so that neighbouring threads hit different banks)
+        for (int i = tid; i < G * BINS; i += kThreads) {
+            uint32_t s = 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r) s += hist[i * R + ((r + i) & (R - 1))];
+            cum[i] = s;
         }
         __syncthreads();
-        if (tid == kThreads - 1) { carry_lt = plt + slt; carry_eq = peq + seq; }
+        for (int i = tid; i < G * BINS * R; i += kThreads) hist[i] = 0;  // ready for the next task
+
+        // cumulative histogram per head (one wave per head), and the block-local candidate bound:
+        // the first distance at which about twice the block's fair share of k (plus a little) is reached
+        const uint32_t want = static_cast<uint32_t>(min(static_cast<int64_t>(n_blk),
+            (static_cast<int64_t>(n_blk) * a.k * 2 + a.n_tokens - 1) / a.n_tokens + 32));
+        for (int g = wave; g < G; g += kThreads / 64) {
+            uint32_t v[CH];
+            uint32_t tot = 0;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int bin = lane * CH + c;
+                tot += bin < BINS ? cum[g * BINS + bin] : 0u;
+                v[c] = tot;
+            }
+            uint32_t inc = tot;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t up = __shfl_up(inc, off);
+                if (lane >= off) inc += up;
+            }
+            const uint32_t before = inc - tot;
+            uint32_t prev = before;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int bin = lane * CH + c;
+                if (bin < BINS) {
+                    const uint32_t cv = before + v[c];
+                    cum[g * BINS + bin] = cv;
+                    gacc[g * BINS + bin] += cv;
+                    if (cv >= want && prev < want) s_thi[g] = static_cast<uint32_t>(bin);  // exactly one bin
+                    prev = cv;
+                }
+            }
+        }
         __syncthreads();
+
+        // publish: the block's cumulative histogram (contiguous store), and, at the end of a run of
+        // tasks of one head group, the accumulated histogram into the head's global one
+        const bool flush = task + 1 == task1 || (task + 1) / a.nblk != bk;
+        for (int i = tid; i < G * BINS; i += kThreads) {
+            const int g = i / BINS, bin = i % BINS;
+            a.blockcum[((bh0 + g) * a.max_blocks + blk) * BINS + bin] = cum[i];
+            if (flush) {
+                const uint32_t v = gacc[i];
+                if (v) atomicAdd(&a.gcum[(bh0 + g) * BINS + bin], v);
+                gacc[i] = 0;
+            }
+        }
+
+        // candidate lists, one sub-list per wavefront: positions from ballots, any fixed order
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const uint32_t thi = s_thi[g];
+            const int64_t slot = (bh0 + g) * a.max_blocks + blk;
+            uint32_t* cl = a.cand + (slot * (kThreads / 64) + wave) * kWaveCap;
+            uint32_t run = 0;
+#pragma unroll
+            for (int i = 0; i < kKPT; ++i) {
+                const uint32_t d = (dv[g][i >> 1] >> ((i & 1) * 16)) & 0xffffu;
+                const bool p = d <= thi;
+                const unsigned long long m = __ballot(p);
+                if (p) {
+                    const uint32_t at = run + __builtin_popcountll(m & ((1ull << lane) - 1ull));
+                    if (at < static_cast<uint32_t>(kWaveCap)) cl[at] = (d << 16) | static_cast<uint32_t>(i * kThreads + tid);
+                }
+                run += __builtin_popcountll(m);
+            }
+            if (lane == 0) {
+                BlockMeta* bm = a.blockmeta + slot;
+                bm->count[wave] = run < static_cast<uint32_t>(kWaveFull) ? static_cast<uint8_t>(run) : static_cast<uint8_t>(kWaveFull);
+                if (wave == 0) bm->bound = thi;
+            }
+        }
+        // the next task's first barrier orders these reads of cum / s_thi / gacc before their reuse
     }
 }
 
 // ------------------------------------------------------------------------------------ select
-// One thread owns 16 consecutive tokens; the workgroup owns tokens_per_block (<= 4096) tokens.
-template <typename DistT>
-__global__ __launch_bounds__(kThreads) void select_kernel(
-    const DistT* __restrict__ dist, const uint2* __restrict__ blockinfo, const uint2* __restrict__ headinfo,
-    int32_t* __restrict__ out_idx, int64_t n_tokens, int64_t dist_stride, int tokens_per_block, int max_blocks, int k)
+constexpr int kSelThreads = 128;  // one thread per 32 tokens of the block
+
+template <int W>
+__global__ __launch_bounds__(kSelThreads) void select_kernel(
+    const uint32_t* __restrict__ codes, const uint32_t* __restrict__ qcode, const uint32_t* __restrict__ gcum,
+    const uint32_t* __restrict__ blockcum, const BlockMeta* __restrict__ blockmeta, const uint32_t* __restrict__ cand,
+    int32_t* __restrict__ out_idx, int64_t n_tokens, int64_t Nmax, int Hq, int Hkv, int max_blocks, int k)
 {
-    __shared__ uint32_t wave_a[kThreads / 64], wave_b[kThreads / 64];
+    constexpr int BINS = W * 32 + 1;
+    constexpr int NW = kSelThreads / 64;
+    constexpr int SUB = kThreads / 64;               // candidate sub-lists per block
+    constexpr int PER = kWaveCap / kSelThreads;      // sub-list entries per thread (2)
+    static_assert(kTPB / 32 == kSelThreads, "one bitmap word per thread");
+    __shared__ uint32_t s_T, s_r;
+    __shared__ uint32_t red[2][NW];
+    __shared__ uint32_t lt_bits[kSelThreads], eq_bits[kSelThreads];
+    __shared__ uint32_t wsum[NW];
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t bh = blockIdx.y;
     const int blk = blockIdx.x;
-    const uint2 info = blockinfo[bh * max_blocks + blk];
-    const uint32_t T = headinfo[bh].x;
-    const uint32_t quota = info.y;
+    const uint32_t* gc = gcum + bh * BINS;
+    const uint32_t* bc = blockcum + bh * max_blocks * BINS;
+    const int64_t slot = bh * max_blocks + blk;
+    const BlockMeta meta = blockmeta[slot];
 
-    const int64_t t_begin = static_cast<int64_t>(blk) * tokens_per_block;
-    const int64_t t_end = min(n_tokens, t_begin + tokens_per_block);
-    const int64_t t0 = t_begin + static_cast<int64_t>(tid) * 16;
-    const DistT* dp = dist + bh * dist_stride;
+    // the candidate entries are fetched before the threshold is known, so that their latency
+    // overlaps the threshold search
+    uint32_t ce[SUB][PER];
+#pragma unroll
+    for (int s = 0; s < SUB; ++s)
+#pragma unroll
+        for (int h = 0; h < PER; ++h) {
+            ce[s][h] = 0;
+            if (meta.count[s] != kWaveFull && h * kSelThreads + tid < static_cast<int>(meta.count[s]))
+                ce[s][h] = cand[(slot * SUB + s) * kWaveCap + h * kSelThreads + tid];
+        }
 
-    uint32_t d[16];
-    if (t0 + 16 <= t_end && tid * 16 < tokens_per_block) {
-        if constexpr (sizeof(DistT) == 1) {
-            const uint4 v = *reinterpret_cast<const uint4*>(dp + t0);
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int i = 0; i < 16; ++i) d[i] = (w[i >> 2] >> ((i & 3) * 8)) & 0xffu;
-        } else {
-            const uint4 v0 = reinterpret_cast<const uint4*>(dp + t0)[0];
-            const uint4 v1 = reinterpret_cast<const uint4*>(dp + t0)[1];
-            const uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-#pragma unroll
-            for (int i = 0; i < 16; ++i) d[i] = (w[i >> 1] >> ((i & 1) * 16)) & 0xffffu;
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int64_t t = t0 + i;
-            d[i] = (t < t_end && tid * 16 < tokens_per_block) ? static_cast<uint32_t>(dp[t]) : 0xffffffffu;
-        }
+    lt_bits[tid] = 0;
+    eq_bits[tid] = 0;
+    for (int bin = tid; bin < BINS; bin += kSelThreads) {
+        const uint32_t c = gc[bin];
+        const uint32_t p = bin ? gc[bin - 1] : 0u;
+        if (c >= static_cast<uint32_t>(k) && p < static_cast<uint32_t>(k)) { s_T = bin; s_r = static_cast<uint32_t>(k) - p; }
     }
+    __syncthreads();
+    const uint32_t T = s_T, r = s_r;
+
+    // tokens below T and in the tie bucket, in the blocks before this one
     uint32_t lt = 0, eq = 0;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { lt += d[i] < T; eq += d[i] == T; }
-
-    // exclusive prefix of eq over threads (token order)
-    uint32_t seq = eq;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t a = __shfl_up(seq, off);
-        if (lane >= off) seq += a;
+    for (int j = tid; j < blk; j += kSelThreads) {
+        const uint32_t le = bc[static_cast<int64_t>(j) * BINS + T];
+        const uint32_t l = T ? bc[static_cast<int64_t>(j) * BINS + T - 1] : 0u;
+        lt += l;
+        eq += le - l;
     }
-    if (lane == 63) wave_a[wave] = seq;
-    __syncthreads();
-    uint32_t eq_before = seq - eq;
-    for (int w = 0; w < wave; ++w) eq_before += wave_a[w];
-    const uint32_t take_eq = quota > eq_before ? min(quota - eq_before, eq) : 0u;
-    const uint32_t cnt = lt + take_eq;
-
-    uint32_t scnt = cnt;
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t a = __shfl_up(scnt, off);
-        if (lane >= off) scnt += a;
-    }
-    if (lane == 63) wave_b[wave] = scnt;
+    for (int off = 32; off >= 1; off >>= 1) { lt += __shfl_xor(lt, off); eq += __shfl_xor(eq, off); }
+    if (lane == 0) { red[0][wave] = lt; red[1][wave] = eq; }
     __syncthreads();
-    uint32_t pos = info.x + scnt - cnt;
-    for (int w = 0; w < wave; ++w) pos += wave_b[w];
+    lt = red[0][0] + red[0][1];
+    eq = red[1][0] + red[1][1];
+    const uint32_t own_le = bc[static_cast<int64_t>(blk) * BINS + T];
+    const uint32_t own_lt = T ? bc[static_cast<int64_t>(blk) * BINS + T - 1] : 0u;
+    const uint32_t own_eq = own_le - own_lt;
+    // Ties go to earlier blocks first.  Written without any subtraction that could wrap.
+    const uint32_t taken_before = eq < r ? eq : r;              // ties taken by the blocks before
+    const uint32_t left = r - taken_before;                     // ties still to hand out
+    const uint32_t quota = left < own_eq ? left : own_eq;       // ties this block may take
+    uint32_t pos = lt + taken_before;                           // output offset of this block
+    if (own_lt + quota == 0) return;                            // uniform over the workgroup
 
-    if (cnt) {
-        int32_t* op = out_idx + bh * k;
-        uint32_t eq_left = take_eq;
+    const int64_t t_begin = static_cast<int64_t>(blk) * kTPB;
+    const int n_blk = static_cast<int>(min(static_cast<int64_t>(kTPB), n_tokens - t_begin));
+    bool listed = T <= meta.bound;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            bool keep = d[i] < T;
-            if (d[i] == T && eq_left) { keep = true; --eq_left; }
-            if (keep && pos < static_cast<uint32_t>(k)) { op[pos] = static_cast<int32_t>(t0 + i); ++pos; }
+    for (int s = 0; s < SUB; ++s) listed = listed && meta.count[s] != kWaveFull;
+    if (listed) {
+#pragma unroll
+        for (int s = 0; s < SUB; ++s)
+#pragma unroll
+            for (int h = 0; h < PER; ++h) {
+                if (h * kSelThreads + tid < static_cast<int>(meta.count[s])) {
+                    const uint32_t d = ce[s][h] >> 16, off = ce[s][h] & 0xffffu;
+                    if (d < T) atomicOr(&lt_bits[off >> 5], 1u << (off & 31));
+                    else if (d == T) atomicOr(&eq_bits[off >> 5], 1u << (off & 31));
+                }
+            }
+    } else {
+        // recompute this block's distances from the codes
+        const int G = Hq / Hkv;
+        const int b = static_cast<int>(bh / Hq), hq = static_cast<int>(bh % Hq);
+        const char* cbase = reinterpret_cast<const char*>(codes + ((static_cast<int64_t>(b) * Hkv + hq / G) * Nmax + t_begin) * W);
+        uint32_t qc[W];
+#pragma unroll
+        for (int w = 0; w < W; ++w) qc[w] = qcode[bh * W + w];
+        for (int off = tid; off < n_blk; off += kSelThreads) {
+            uint32_t kw[W];
+            load_key<W>(cbase, static_cast<uint32_t>(off) * (W * 4), kw);
+            uint32_t d = 0;
+#pragma unroll
+            for (int w = 0; w < W; ++w) d += popc(kw[w] ^ qc[w]);
+            if (d < T) atomicOr(&lt_bits[off >> 5], 1u << (off & 31));
+            else if (d == T) atomicOr(&eq_bits[off >> 5], 1u << (off & 31));
         }
+    }
+    __syncthreads();
+
+    // thread j owns tokens 32j .. 32j+31 of the block
+    const uint32_t lw = lt_bits[tid];
+    uint32_t ew = eq_bits[tid];
+    const uint32_t ecount = popc(ew);
+    uint32_t sc = ecount;  // inclusive scan of tie counts over threads (token order)
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = __shfl_up(sc, off);
+        if (lane >= off) sc += up;
+    }
+    if (lane == 63) wsum[wave] = sc;
+    __syncthreads();
+    uint32_t eq_before = sc - ecount;
+    if (wave == 1) eq_before += wsum[0];
+    const uint32_t gone = eq_before < quota ? eq_before : quota;  // quota used by earlier threads
+    const uint32_t take = (quota - gone) < ecount ? (quota - gone) : ecount;
+    while (static_cast<uint32_t>(popc(ew)) > take) ew &= ~(0x80000000u >> __builtin_clz(ew));  // drop the highest ties
+    uint32_t sel = lw | ew;
+    const uint32_t cnt = popc(sel);
+    __syncthreads();  // wsum is reused
+    uint32_t sn = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = __shfl_up(sn, off);
+        if (lane >= off) sn += up;
+    }
+    if (lane == 63) wsum[wave] = sn;
+    __syncthreads();
+    pos += sn - cnt;
+    if (wave == 1) pos += wsum[0];
+    int32_t* op = out_idx + bh * k;
+    const int32_t tok0 = static_cast<int32_t>(t_begin) + tid * 32;
+    while (sel) {
+        const int bit = __builtin_ctz(sel);
+        sel &= sel - 1;
+        if (pos < static_cast<uint32_t>(k)) op[pos] = tok0 + bit;
+        ++pos;
     }
 }
 
-template <typename DistT>
-__global__ __launch_bounds__(kThreads) void dump_dist_kernel(const DistT* __restrict__ dist, uint16_t* __restrict__ out,
-                                                             int64_t n_tokens, int64_t dist_stride)
+// All distances of every query head, for tests and debugging only.
+template <int W>
+__global__ __launch_bounds__(kThreads) void dist_kernel(const uint32_t* __restrict__ codes,
+                                                        const uint32_t* __restrict__ qcode,
+                                                        uint16_t* __restrict__ out, int64_t n_tokens,
+                                                        int64_t Nmax, int Hq, int Hkv)
 {
     const int64_t bh = blockIdx.y;
     const int64_t t = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (t < n_tokens) out[bh * n_tokens + t] = static_cast<uint16_t>(dist[bh * dist_stride + t]);
+    if (t >= n_tokens) return;
+    const int b = static_cast<int>(bh / Hq), hq = static_cast<int>(bh % Hq);
+    const uint32_t* p = codes + ((static_cast<int64_t>(b) * Hkv + hq / (Hq / Hkv)) * Nmax + t) * W;
+    int d = 0;
+#pragma unroll
+    for (int w = 0; w < W; ++w) d += popc(p[w] ^ qcode[bh * W + w]);
+    out[bh * n_tokens + t] = static_cast<uint16_t>(d);
 }
 
 // ------------------------------------------------------------------------------------ dispatch
-template <int W, int G, typename DistT>
-void launch_score_wg(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens, int nblk)
+struct RetrieveArgs {
+    const uint32_t* codes;
+    int64_t n_tokens;
+    int k, nblk;
+    int32_t* out_idx;
+    uint16_t* out_dist;
+};
+
+template <int W, int G>
+int launch_score_wg(spotlight_ctx* ctx, const RetrieveArgs& a)
 {
     const Plan& p = ctx->plan;
     constexpr int BINS = W * 32 + 1;
-    // replicas: as many as fit in 40 KB of LDS, at most 32
-    constexpr int kCap = 40960;
+    // histogram replicas: as many as fit in 32 KB of LDS, at most 32
+    constexpr int kCap = 32768;
     constexpr int R = (G * BINS * 32 * 4 <= kCap) ? 32 : (G * BINS * 16 * 4 <= kCap) ? 16
                     : (G * BINS * 8 * 4 <= kCap) ? 8 : (G * BINS * 4 * 4 <= kCap) ? 4
                     : (G * BINS * 2 * 4 <= kCap) ? 2 : 1;
-    dim3 grid(static_cast<unsigned>(nblk), static_cast<unsigned>(p.B * p.Hkv));
-    hipLaunchKernelGGL((score_kernel<W, G, DistT, R>), grid, dim3(kThreads), 0, ctx->stream, codes,
-                       reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_qcode),
-                       reinterpret_cast<DistT*>(ctx->workspace + p.off_dist),
-                       reinterpret_cast<uint32_t*>(ctx->workspace + p.off_blockhist), n_tokens, p.Nmax,
-                       p.dist_stride, p.Hkv, p.tokens_per_block, p.max_blocks);
-}
-
-template <int W, int G>
-void launch_score_w(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens, int nblk)
-{
-    if constexpr (W * 32 < 256) launch_score_wg<W, G, uint8_t>(ctx, codes, n_tokens, nblk);
-    else launch_score_wg<W, G, uint16_t>(ctx, codes, n_tokens, nblk);
+    auto kern = score_kernel<W, G, R>;
+    // persistent grid: as many workgroups as the chip holds at once
+    static int resident = 0;  // per instantiation; the library drives one kind of device
+    if (resident == 0) {
+        int per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kThreads, 0) != hipSuccess || per_cu < 1)
+            return SPOTLIGHT_ERR_HIP;
+        resident = per_cu * ctx->n_cus;
+    }
+    ScoreArgs s;
+    s.codes = a.codes;
+    s.qcode = reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_qcode);
+    s.gcum = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_gcum);
+    s.blockcum = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_blockcum);
+    s.blockmeta = reinterpret_cast<BlockMeta*>(ctx->workspace + p.off_blockmeta);
+    s.cand = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_cand);
+    s.n_tokens = a.n_tokens;
+    s.Nmax = p.Nmax;
+    s.Hkv = p.Hkv;
+    s.nblk = a.nblk;
+    s.max_blocks = p.max_blocks;
+    s.k = a.k;
+    s.total_tasks = a.nblk * p.B * p.Hkv;
+    s.tasks_per_group = (s.total_tasks + resident - 1) / resident;
+    const int grid = (s.total_tasks + s.tasks_per_group - 1) / s.tasks_per_group;
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), 0, ctx->stream, s);
+    return SPOTLIGHT_OK;
 }
 
 template <int W>
-int launch_score_g(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens, int nblk)
-{
-    switch (ctx->plan.G) {
-    case 1: launch_score_w<W, 1>(ctx, codes, n_tokens, nblk); return SPOTLIGHT_OK;
-    case 2: launch_score_w<W, 2>(ctx, codes, n_tokens, nblk); return SPOTLIGHT_OK;
-    case 4: launch_score_w<W, 4>(ctx, codes, n_tokens, nblk); return SPOTLIGHT_OK;
-    case 8: launch_score_w<W, 8>(ctx, codes, n_tokens, nblk); return SPOTLIGHT_OK;
-    default: return SPOTLIGHT_ERR_UNSUPPORTED;
-    }
-}
-
-int launch_score(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens, int nblk)
-{
-    switch (ctx->plan.W) {
-    case 1: return launch_score_g<1>(ctx, codes, n_tokens, nblk);
-    case 2: return launch_score_g<2>(ctx, codes, n_tokens, nblk);
-    case 3: return launch_score_g<3>(ctx, codes, n_tokens, nblk);
-    case 4: return launch_score_g<4>(ctx, codes, n_tokens, nblk);
-    case 5: return launch_score_g<5>(ctx, codes, n_tokens, nblk);
-    case 6: return launch_score_g<6>(ctx, codes, n_tokens, nblk);
-    case 7: return launch_score_g<7>(ctx, codes, n_tokens, nblk);
-    case 8: return launch_score_g<8>(ctx, codes, n_tokens, nblk);
-    case 9: return launch_score_g<9>(ctx, codes, n_tokens, nblk);
-    case 10: return launch_score_g<10>(ctx, codes, n_tokens, nblk);
-    case 11: return launch_score_g<11>(ctx, codes, n_tokens, nblk);
-    case 12: return launch_score_g<12>(ctx, codes, n_tokens, nblk);
-    case 13: return launch_score_g<13>(ctx, codes, n_tokens, nblk);
-    case 14: return launch_score_g<14>(ctx, codes, n_tokens, nblk);
-    case 15: return launch_score_g<15>(ctx, codes, n_tokens, nblk);
-    case 16: return launch_score_g<16>(ctx, codes, n_tokens, nblk);
-    default: return SPOTLIGHT_ERR_UNSUPPORTED;
-    }
-}
-
-}  // namespace
-
-int launch_retrieve(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens, int k,
-                    int32_t* out_idx, uint16_t* out_dist)
+int launch_w(spotlight_ctx* ctx, const RetrieveArgs& a)
 {
     const Plan& p = ctx->plan;
-    const int nblk = static_cast<int>((n_tokens + p.tokens_per_block - 1) / p.tokens_per_block);
     const int BH = p.B * p.Hq;
-    uint2* blockinfo = reinterpret_cast<uint2*>(ctx->workspace + p.off_blockinfo);
-    uint2* headinfo = reinterpret_cast<uint2*>(ctx->workspace + p.off_headinfo);
+    const uint32_t* qcode = reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_qcode);
     {
         StageTimer timer(ctx, SPOTLIGHT_STAGE_SCORE);
-        const int rc = launch_score(ctx, codes, n_tokens, nblk);
+        int rc;
+        switch (p.G) {
+        case 1: rc = launch_score_wg<W, 1>(ctx, a); break;
+        case 2: rc = launch_score_wg<W, 2>(ctx, a); break;
+        case 4: rc = launch_score_wg<W, 4>(ctx, a); break;
+        case 8: rc = launch_score_wg<W, 8>(ctx, a); break;
+        default: return SPOTLIGHT_ERR_UNSUPPORTED;
+        }
         if (rc != SPOTLIGHT_OK) return rc;
         if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
     }
     {
-        StageTimer timer(ctx, SPOTLIGHT_STAGE_SCAN);
-        hipLaunchKernelGGL(scan_kernel, dim3(BH), dim3(kThreads), 0, ctx->stream,
-                           reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_blockhist), blockinfo, headinfo,
-                           p.L + 1, nblk, p.max_blocks, k);
-        if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
-    }
-    {
         StageTimer timer(ctx, SPOTLIGHT_STAGE_SELECT);
-        dim3 grid(static_cast<unsigned>(nblk), static_cast<unsigned>(BH));
-        if (p.dist_bytes == 1)
-            hipLaunchKernelGGL(select_kernel<uint8_t>, grid, dim3(kThreads), 0, ctx->stream,
-                               reinterpret_cast<const uint8_t*>(ctx->workspace + p.off_dist), blockinfo, headinfo,
-                               out_idx, n_tokens, p.dist_stride, p.tokens_per_block, p.max_blocks, k);
-        else
-            hipLaunchKernelGGL(select_kernel<uint16_t>, grid, dim3(kThreads), 0, ctx->stream,
-                               reinterpret_cast<const uint16_t*>(ctx->workspace + p.off_dist), blockinfo, headinfo,
-                               out_idx, n_tokens, p.dist_stride, p.tokens_per_block, p.max_blocks, k);
+        dim3 grid(static_cast<unsigned>(a.nblk), static_cast<unsigned>(BH));
+        hipLaunchKernelGGL(select_kernel<W>, grid, dim3(kSelThreads), 0, ctx->stream, a.codes, qcode,
+                           reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_gcum),
+                           reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_blockcum),
+                           reinterpret_cast<const BlockMeta*>(ctx->workspace + p.off_blockmeta),
+                           reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_cand), a.out_idx, a.n_tokens,
+                           p.Nmax, p.Hq, p.Hkv, p.max_blocks, a.k);
         if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
     }
-    if (out_dist) {
-        dim3 grid(static_cast<unsigned>((n_tokens + kThreads - 1) / kThreads), static_cast<unsigned>(BH));
-        if (p.dist_bytes == 1)
-            hipLaunchKernelGGL(dump_dist_kernel<uint8_t>, grid, dim3(kThreads), 0, ctx->stream,
-                               reinterpret_cast<const uint8_t*>(ctx->workspace + p.off_dist), out_dist, n_tokens, p.dist_stride);
-        else
-            hipLaunchKernelGGL(dump_dist_kernel<uint16_t>, grid, dim3(kThreads), 0, ctx->stream,
-                               reinterpret_cast<const uint16_t*>(ctx->workspace + p.off_dist), out_dist, n_tokens, p.dist_stride);
+    if (a.out_dist) {
+        dim3 grid(static_cast<unsigned>((a.n_tokens + kThreads - 1) / kThreads), static_cast<unsigned>(BH));
+        hipLaunchKernelGGL(dist_kernel<W>, grid, dim3(kThreads), 0, ctx->stream, a.codes, qcode, a.out_dist,
+                           a.n_tokens, p.Nmax, p.Hq, p.Hkv);
         if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
     }
     return SPOTLIGHT_OK;
+}
+
+}  // namespace
+
+int launch_retrieve(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens, int k, int32_t* out_idx,
+                    uint16_t* out_dist)
+{
+    RetrieveArgs a;
+    a.codes = codes;
+    a.n_tokens = n_tokens;
+    a.k = k;
+    a.nblk = static_cast<int>((n_tokens + kTPB - 1) / kTPB);
+    a.out_idx = out_idx;
+    a.out_dist = out_dist;
+    switch (ctx->plan.W) {
+    case 1: return launch_w<1>(ctx, a);
+    case 2: return launch_w<2>(ctx, a);
+    case 3: return launch_w<3>(ctx, a);
+    case 4: return launch_w<4>(ctx, a);
+    case 5: return launch_w<5>(ctx, a);
+    case 6: return launch_w<6>(ctx, a);
+    case 7: return launch_w<7>(ctx, a);
+    case 8: return launch_w<8>(ctx, a);
+    case 9: return launch_w<9>(ctx, a);
+    case 10: return launch_w<10>(ctx, a);
+    case 11: return launch_w<11>(ctx, a);
+    case 12: return launch_w<12>(ctx, a);
+    case 13: return launch_w<13>(ctx, a);
+    case 14: return launch_w<14>(ctx, a);
+    case 15: return launch_w<15>(ctx, a);
+    case 16: return launch_w<16>(ctx, a);
+    default: return SPOTLIGHT_ERR_UNSUPPORTED;
+    }
 }
 
 }  // namespace spotlight
