@@ -1,0 +1,203 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+The oracle cannot hash every key of the large configs in test time, so:
+  * key codes are checked bit-exactly on whole sampled heads (C2: all heads) or sampled rows (C5);
+  * retrieval is checked bit-exactly on EVERY head from seeded synthetic code caches (both sides
+    read the same generated codes), and on the sampled heads from real hashed codes;
+  * attention is checked on every head against the oracle run on the gathered rows;
+  * on the remaining heads of the real chain, properties that hold at any size are checked
+    (k distinct ascending in-range indices, planted needles present).
+Inputs come from the seeded generator only; nothing computed by the HIP path feeds the oracle.
+"""
+import math
+
+import pytest
+import torch
+
+import oracle
+import workload as wl
+from gpu_common import torch_dtype
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+ATTN_TOL = 2e-3
+DEV = "cuda:0"
+
+
+class Big:
+    """Device tensors of a full-size config; host copies only of what a check needs."""
+
+    def __init__(self, cfg, need_kv=True):
+        import paper_2508_19740_amd as sp
+        self.cfg = cfg
+        self.w = wl.Workload(cfg)
+        self.K = self.w.materialize("K", DEV) if need_kv else None
+        self.V = self.w.materialize("V", DEV) if need_kv else None
+        self.q = self.w.q.to(DEV)
+        self.hweights = self.w.hash_weights()
+        self.weights = tuple(None if t is None else t.to(DEV) for t in self.hweights)
+        self.codes = torch.zeros(cfg.batch, cfg.n_kv_heads, cfg.max_tokens, cfg.words, dtype=torch.int32, device=DEV)
+        self.ctx = sp.Spotlight(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.code_bits, cfg.hidden,
+                                cfg.max_tokens, cfg.topk, kv_dtype=torch_dtype(cfg.kv_dtype),
+                                weight_dtype=torch_dtype(cfg.weight_dtype), device=DEV)
+        self.scale = 1.0 / math.sqrt(cfg.head_dim)
+
+    def head_weights(self, hk):
+        return tuple(None if t is None else t[hk].contiguous() for t in self.hweights)
+
+    def synthetic_codes(self):
+        c = self.cfg
+        out = torch.empty_like(self.codes)
+        for b in range(c.batch):
+            for hk in range(c.n_kv_heads):
+                out[b, hk] = self.w.synthetic_codes(b, hk, 0, c.max_tokens, DEV)
+        return out
+
+    def close(self):
+        self.ctx.close()
+
+
+def check_index_properties(idx, cfg, needle_pos=None):
+    """k distinct, ascending, in-range indices per head (and the planted needles among them)."""
+    i64 = idx.long()
+    assert int(i64.min()) >= 0 and int(i64.max()) < cfg.n_tokens
+    assert bool((i64[..., 1:] > i64[..., :-1]).all())
+    if needle_pos is not None and needle_pos.numel():
+        for b in range(cfg.batch):
+            for hq in range(cfg.n_q_heads):
+                have = set(idx[b, hq].tolist())
+                assert set(needle_pos[b, hq].tolist()) <= have, (b, hq)
+
+
+def check_retrieval_on_synthetic_codes(big, n_tokens=None):
+    """Every head: GPU top-k from generated codes against the oracle's full sort of the same codes."""
+    c = big.cfg
+    n = c.n_tokens if n_tokens is None else n_tokens
+    dcodes = big.synthetic_codes()
+    qcode = torch.empty(c.batch, c.n_q_heads, c.words, dtype=torch.int32, device=DEV)
+    idx = big.ctx.retrieve_topk(big.q, *big.weights, dcodes, n, c.topk, out_qcode=qcode).cpu()
+    qc = qcode.cpu()
+    G = c.group
+    for b in range(c.batch):
+        for hk in range(c.n_kv_heads):
+            hc = dcodes[b, hk, :n].cpu().contiguous()
+            for g in range(G):
+                hq = hk * G + g
+                # the query code itself is pinned against the oracle's hash of q
+                _, want_q = oracle.hash_rows(big.w.q[b, hq:hq + 1].contiguous(), *big.head_weights(hk), c.code_bits)
+                assert torch.equal(qc[b, hq], want_q[0]), (b, hq)
+                dist = oracle.hamming(want_q[0].contiguous(), hc)
+                want = oracle.topk(dist, c.topk)
+                assert torch.equal(idx[b, hq], want), (b, hq)
+    return idx
+
+
+def check_attention_all_heads(big, idx_host):
+    """Every head: GPU attention over idx against the oracle on the gathered rows."""
+    c = big.cfg
+    didx = idx_host.to(DEV)
+    out = big.ctx.sparse_decode(big.q, big.K, big.V, didx, big.scale).cpu()
+    G = c.group
+    ar = torch.arange(c.topk, dtype=torch.int32)
+    worst = 0.0
+    for b in range(c.batch):
+        for hq in range(c.n_q_heads):
+            sel = didx[b, hq].long()
+            Ks = big.K[b, hq // G].index_select(0, sel).cpu()
+            Vs = big.V[b, hq // G].index_select(0, sel).cpu()
+            want = oracle.sparse_attention(big.w.q[b, hq].contiguous(), Ks, Vs, ar, big.scale)
+            worst = max(worst, float((out[b, hq] - want).abs().max()))
+    assert worst <= ATTN_TOL, worst
+
+
+def check_sampled_heads_real_chain(big, heads):
+    """Whole heads through hash -> retrieve -> attend on both sides; the GPU ran every head."""
+    c = big.cfg
+    G = c.group
+    big.codes.zero_()
+    big.ctx.hash_keys(big.K, *big.weights, 0, c.n_tokens, big.codes)
+    idx = big.ctx.retrieve_topk(big.q, *big.weights, big.codes, c.n_tokens, c.topk)
+    out = big.ctx.sparse_decode(big.q, big.K, big.V, idx, big.scale).cpu()
+    idx_h = idx.cpu()
+    check_index_properties(idx_h, c, big.w.needle_pos)
+    for (b, hk) in heads:
+        hK = big.K[b, hk, :c.n_tokens].cpu()
+        hV = big.V[b, hk, :c.n_tokens].cpu()
+        _, want_codes = oracle.hash_rows(hK, *big.head_weights(hk), c.code_bits)
+        assert torch.equal(big.codes[b, hk, :c.n_tokens].cpu(), want_codes), (b, hk)
+        for g in range(G):
+            hq = hk * G + g
+            _, qc = oracle.hash_rows(big.w.q[b, hq:hq + 1].contiguous(), *big.head_weights(hk), c.code_bits)
+            dist = oracle.hamming(qc[0].contiguous(), want_codes)
+            want_idx = oracle.topk(dist, c.topk)
+            assert torch.equal(idx_h[b, hq], want_idx), (b, hq)
+            want = oracle.sparse_attention(big.w.q[b, hq].contiguous(), hK, hV, want_idx, big.scale)
+            assert float((out[b, hq] - want).abs().max()) <= ATTN_TOL, (b, hq)
+    return idx_h
+
+
+def test_c2_every_head_against_the_full_oracle():
+    big = Big(wl.CONFIGS["C2"])
+    try:
+        c = big.cfg
+        idx = check_sampled_heads_real_chain(big, [(0, h) for h in range(c.n_kv_heads)])
+        check_attention_all_heads(big, idx)
+    finally:
+        big.close()
+
+
+def test_c3_512k_tokens():
+    big = Big(wl.CONFIGS["C3"])
+    try:
+        idx = check_sampled_heads_real_chain(big, [(0, 5), (0, 31)])
+        check_attention_all_heads(big, idx)
+        check_retrieval_on_synthetic_codes(big)
+    finally:
+        big.close()
+
+
+def test_c4_gqa_batch16():
+    big = Big(wl.CONFIGS["C4"])
+    try:
+        idx = check_sampled_heads_real_chain(big, [(0, 0), (9, 3), (15, 7)])
+        check_attention_all_heads(big, idx)
+        check_retrieval_on_synthetic_codes(big)
+    finally:
+        big.close()
+
+
+@pytest.fixture(scope="module")
+def c5_kv():
+    """K and V of config C5 (the 128-bit and 512-bit variants share them): 2 x 34 GB on the device."""
+    w = wl.Workload(wl.CONFIGS["C5-128"])
+    return w.materialize("K", DEV), w.materialize("V", DEV)
+
+
+@pytest.mark.parametrize("name", ["C5-128", "C5-512"])
+def test_c5_one_million_tokens_with_growth(c5_kv, name):
+    big = Big(wl.CONFIGS[name], need_kv=False)
+    big.K, big.V = c5_kv
+    try:
+        c = big.cfg
+        N = c.n_tokens
+        # bulk build, then three decode-step appends
+        big.ctx.hash_keys(big.K, *big.weights, 0, N, big.codes)
+        for j in range(3):
+            big.ctx.hash_keys(big.K, *big.weights, N + j, 1, big.codes)
+        # sampled rows of sampled heads, including both ends, a tile boundary and the appended keys
+        gen = torch.Generator().manual_seed(7)
+        rows = torch.cat([torch.arange(0, 40), torch.arange(N // 2 - 20, N // 2 + 20), torch.arange(N - 40, N + 3),
+                          torch.randint(0, N, (400,), generator=gen)]).unique()
+        for (b, hk) in [(0, 0), (2, 17), (3, 31)]:
+            x = big.K[b, hk].index_select(0, rows.to(DEV)).cpu()
+            _, want = oracle.hash_rows(x, *big.head_weights(hk), c.code_bits)
+            got = big.codes[b, hk].index_select(0, rows.to(DEV)).cpu()
+            assert torch.equal(got, want), (b, hk)
+        assert int(big.codes[:, :, N + 3:].abs().max()) == 0          # rows never hashed stay untouched
+        # the real chain over the grown cache: properties on every head
+        idx = big.ctx.retrieve_topk(big.q, *big.weights, big.codes, N + 3, c.topk).cpu()
+        check_index_properties(idx, c.scaled(n_tokens=N + 3), big.w.needle_pos)
+        check_attention_all_heads(big, idx)
+        # exact retrieval on every head from generated codes, over a ragged token count
+        check_retrieval_on_synthetic_codes(big, n_tokens=N + 3)
+    finally:
+        big.close()
