@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="independent layers to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=2, help="heads in the oracle's timed sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run 10 plain device copies of 1 GiB (a kernel of known HBM traffic, for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -119,6 +122,14 @@ def main():
         if ev:
             ev[2].record()
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.int32, device=dev).fill_(7)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -163,6 +174,19 @@ def main():
     # attention: K and V row per selected token, its index, q in, out written
     attend_bytes = B * Hq * k * (2 * d * esz + 4) + B * Hq * d * (esz + 4)
 
+    def traffic(kernel):
+        """HBM bytes per launch measured with rocprofv3 counters for this workload, or None."""
+        path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+        if not os.path.exists(path):
+            return None
+        for line in open(path):
+            f = line.split()
+            if len(f) == 6 and f[0] == args.config and f[1] == kernel:
+                kv = dict(x.split("=") for x in f[2:])
+                return int(1024 * (float(kv["fetch_kib"]) * float(kv["fetch_scale"]) +
+                                   float(kv["write_kib"]) * float(kv["write_scale"])))
+        return None
+
     def gbps(nbytes, us):
         return nbytes / (us * 1e-6) / 1e9 if us else None
 
@@ -174,19 +198,19 @@ def main():
         "peak": HBM_PEAK_GBPS,
         "unit": "GB/s",
         "frac": round(gbps(score_bytes, score_us) / HBM_PEAK_GBPS, 4),
-        "traffic": None,
+        "traffic": traffic("score_kernel"),
         "bytes_per_launch": score_bytes,
         "avg_launch_us": round(score_us, 2),
         "timing": "HIP events around each launch, second pass over the same steps",
     }
     roofline_attend = {
-        "kernel": "attend_kernel (gather + softmax attention, merge by the last workgroup)",
+        "kernel": "attend_kernel + merge_kernel (gather, split-k softmax attention, merge of the partials)",
         "bound": "hbm",
         "achieved": round(gbps(attend_bytes, stage_us["attend"]), 1),
         "peak": HBM_PEAK_GBPS,
         "unit": "GB/s",
         "frac": round(gbps(attend_bytes, stage_us["attend"]) / HBM_PEAK_GBPS, 4),
-        "traffic": None,
+        "traffic": traffic("attend_kernel"),
         "bytes_per_launch": attend_bytes,
         "avg_launch_us": round(stage_us["attend"], 2),
     }
