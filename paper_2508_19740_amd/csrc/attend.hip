@@ -164,31 +164,34 @@ __global__ __launch_bounds__(kThreads) void attend_kernel(
     }
 }
 
-// Merge of the partials of one head.  256 threads: thread (c, half) owns output column c and the
-// splits of parity `half`, folded in split order with a running maximum.  Loads are issued eight
-// splits at a time, ahead of the arithmetic that depends on them; the two halves are combined at
-// the end.
+// Merge of the partials of a head.  A workgroup owns 32 output columns of one head; thread
+// (c, part) folds the splits part, part + 8, ... of column c in split order with a running maximum
+// (loads issued twelve splits at a time, ahead of the arithmetic), then the eight parts are
+// combined in part order through LDS.  Latency-bound: the point is one round trip to memory.
+constexpr int kMergeCols = 32, kMergeParts = kThreads / kMergeCols;
+
 __global__ __launch_bounds__(kThreads) void merge_kernel(const float2* __restrict__ part_ml,
                                                          const float* __restrict__ part_acc,
                                                          float* __restrict__ out, int nsplit, int max_splits)
 {
-    constexpr int NB = 8;
-    __shared__ float s_m[kHeadDim], s_a[kHeadDim], s_l[kHeadDim];
+    constexpr int NB = 12;
+    __shared__ float s_m[kMergeParts][kMergeCols], s_a[kMergeParts][kMergeCols], s_l[kMergeParts][kMergeCols];
     const int tid = threadIdx.x;
-    const int64_t bh = blockIdx.x;
+    const int64_t bh = blockIdx.y;
+    const int c = tid & (kMergeCols - 1), part = tid / kMergeCols;
+    const int col = blockIdx.x * kMergeCols + c;
     const float2* ml = part_ml + bh * max_splits;
-    const float* pa = part_acc + bh * max_splits * kHeadDim;
-    const int c = tid & (kHeadDim - 1), half = tid >> 7;
+    const float* pa = part_acc + bh * max_splits * kHeadDim + col;
     float m = -INFINITY, a = 0.0f, l = 0.0f;
-    for (int s0 = half; s0 < nsplit; s0 += 2 * NB) {
+    for (int s0 = part; s0 < nsplit; s0 += kMergeParts * NB) {
         float2 v[NB];
         float av[NB];
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            const int sp = s0 + 2 * i;
+            const int sp = s0 + kMergeParts * i;
             const int spc = sp < nsplit ? sp : s0;         // in-bounds stand-in, masked below
             v[i] = ml[spc];
-            av[i] = pa[static_cast<int64_t>(spc) * kHeadDim + c];
+            av[i] = pa[static_cast<int64_t>(spc) * kHeadDim];
             if (sp >= nsplit) v[i].x = -INFINITY;
         }
 #pragma unroll
@@ -202,20 +205,22 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float2* __restric
             }
         }
     }
-    if (half == 1) { s_m[c] = m; s_a[c] = a; s_l[c] = l; }
+    s_m[part][c] = m; s_a[part][c] = a; s_l[part][c] = l;
     __syncthreads();
-    if (half == 0) {
-        const float m1 = s_m[c];
-        const float mn = fmaxf(m, m1);
-        float res = 0.0f;
-        if (mn > -INFINITY) {
-            const float f0 = m > -INFINITY ? __expf(m - mn) : 0.0f;
-            const float f1 = m1 > -INFINITY ? __expf(m1 - mn) : 0.0f;
-            const float at = __builtin_fmaf(a, f0, f1 * s_a[c]);
-            const float lt = __builtin_fmaf(l, f0, f1 * s_l[c]);
-            res = lt > 0.0f ? at / lt : 0.0f;
+    if (part == 0) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int p = 0; p < kMergeParts; ++p) M = fmaxf(M, s_m[p][c]);
+        float at = 0.0f, lt = 0.0f;
+        if (M > -INFINITY) {
+#pragma unroll
+            for (int p = 0; p < kMergeParts; ++p) {
+                const float f = s_m[p][c] > -INFINITY ? __expf(s_m[p][c] - M) : 0.0f;
+                at = __builtin_fmaf(f, s_a[p][c], at);
+                lt = __builtin_fmaf(f, s_l[p][c], lt);
+            }
         }
-        out[bh * kHeadDim + c] = res;
+        out[bh * kHeadDim + col] = lt > 0.0f ? at / lt : 0.0f;
     }
 }
 
@@ -247,7 +252,7 @@ int launch_t(spotlight_ctx* ctx, const void* q, const void* K, const void* V, co
     else if (RB == 64) launch_rb<T, 64>(ctx, q, K, V, idx, k, scale, nsplit);
     else launch_rb<T, 32>(ctx, q, K, V, idx, k, scale, nsplit);
     if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
-    hipLaunchKernelGGL(merge_kernel, dim3(static_cast<unsigned>(heads)), dim3(kThreads), 0, ctx->stream,
+    hipLaunchKernelGGL(merge_kernel, dim3(kHeadDim / kMergeCols, static_cast<unsigned>(heads)), dim3(kThreads), 0, ctx->stream,
                        reinterpret_cast<const float2*>(ctx->workspace + p.off_part_ml),
                        reinterpret_cast<const float*>(ctx->workspace + p.off_part_acc), out, nsplit, p.max_splits);
     return hip_rc(hipGetLastError());
