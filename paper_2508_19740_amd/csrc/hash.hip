@@ -230,9 +230,10 @@ __global__ __launch_bounds__(kThreads) void hash_kernel(HashArgs a)
 
 // One vector per workgroup (the query of a head, or the key appended by a decode step), for hidden
 // widths that are multiples of 128 (or the linear hash).  Latency matters here, not throughput: x
-// is read through uniform addresses, and every thread fetches its whole W1 row and the first 256
-// weights of its W2 row (kept in their stored form) before any arithmetic, so a hidden width of
-// 256 costs one round trip to memory.  The only LDS traffic is the broadcast of the hidden
+// is read through uniform addresses, and every thread fetches its whole W1 row and the first 128
+// weights of its W2 row (kept in their stored form) before any arithmetic.  (Fetching more ahead,
+// or staging the weights through LDS with coalesced loads, measured slower: rows are 256 B or more
+// apart, so every 16-byte load of a wave touches 64 cache lines and issue time dominates.)  The only LDS traffic is the broadcast of the hidden
 // activations.  Same arithmetic, same order as the tiled kernel.
 template <typename XT, typename WT>
 __global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashArgs a)
@@ -250,7 +251,7 @@ __global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashArgs a)
                                   : static_cast<const WT*>(a.w1) + static_cast<int64_t>(whead) * a.L * kHeadDim;
     const int npairs = (a.W + 1) / 2;
 
-    // fetch the first two runs of this thread's first output row
+    // fetch the first run of this thread's first output row
     const int word0 = 2 * wave + (lane >> 5);
     const bool live0 = wave < npairs && word0 < a.W;
     const int o0 = live0 ? (31 - (lane & 31)) * a.W + word0 : 0;
@@ -259,10 +260,6 @@ __global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashArgs a)
         const WT* row = wout + static_cast<int64_t>(o0) * act_dim;
 #pragma unroll
         for (int g = 0; g < G16; ++g) load_raw(row + g * 8, ra[g]);
-        if (n16 > 1) {
-#pragma unroll
-            for (int g = 0; g < G16; ++g) load_raw(row + kHeadDim + g * 8, rb[g]);
-        }
     }
 
     if (a.hidden > 0) {
@@ -316,13 +313,13 @@ __global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashArgs a)
         const WT* row = wout + static_cast<int64_t>(o) * act_dim;
         float y = 0.0f;
         for (int r0 = 0; r0 < n16; r0 += 2) {
-            if (pair != wave || r0 != 0) {   // the first two runs of the first row are already here
+            if (pair != wave || r0 != 0) {   // the first run of the first row is already here
 #pragma unroll
                 for (int g = 0; g < G16; ++g) load_raw(row + r0 * kHeadDim + g * 8, ra[g]);
-                if (r0 + 1 < n16) {
+            }
+            if (r0 + 1 < n16) {
 #pragma unroll
-                    for (int g = 0; g < G16; ++g) load_raw(row + (r0 + 1) * kHeadDim + g * 8, rb[g]);
-                }
+                for (int g = 0; g < G16; ++g) load_raw(row + (r0 + 1) * kHeadDim + g * 8, rb[g]);
             }
             y = run128(ra, act + r0 * kHeadDim, y);
             if (r0 + 1 < n16) y = run128(rb, act + (r0 + 1) * kHeadDim, y);
