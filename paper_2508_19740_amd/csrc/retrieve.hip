@@ -86,7 +86,12 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
     constexpr int L = W * 32;
     constexpr int BINS = L + 1;
     constexpr int CH = (BINS + 63) / 64;   // bins per lane in the scan
-    constexpr int KB = W <= 4 ? 4 : (W <= 8 ? 2 : 1);  // keys in flight per lane
+    // lanes per key: 16 bytes per lane when the code is 16, 32 or 64 bytes, else one lane per key
+    constexpr int LPK = (W == 4 || W == 8 || W == 16) ? W / 4 : 1;
+    constexpr int CWL = W / LPK;           // code words per lane
+    constexpr int SLOTS = kKPT * LPK;      // load instructions per thread and task
+    constexpr int KPS = kThreads / LPK;    // keys per slot
+    constexpr int KB = CWL <= 4 ? 4 : (CWL <= 8 ? 2 : 1);  // loads in flight per lane
     __shared__ uint32_t hist[G * BINS * R];
     __shared__ uint32_t cum[G * BINS];     // this block's histogram, then its cumulative form
     __shared__ uint32_t gacc[G * BINS];    // cumulative histogram summed over this run of tasks
@@ -95,7 +100,8 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rep = tid & (R - 1);
     const int Hq = a.Hkv * G;
-    const uint32_t lane_off = static_cast<uint32_t>(tid) * (W * 4);
+    const uint32_t lane_off = static_cast<uint32_t>(tid) * (CWL * 4);
+    const int sub = tid % LPK, kq = tid / LPK;   // part of the key this lane reads, key within a slot
 
     for (int i = tid; i < G * BINS * R; i += kThreads) hist[i] = 0;
     for (int i = tid; i < G * BINS; i += kThreads) gacc[i] = 0;
@@ -111,39 +117,49 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
         const int n_blk = static_cast<int>(min(static_cast<int64_t>(kTPB), a.n_tokens - t_begin));
         const char* base = reinterpret_cast<const char*>(a.codes + (static_cast<int64_t>(bk) * a.Nmax + t_begin) * W);
 
-        uint32_t qc[G][W];  // query codes of the group: uniform over the workgroup
+        // this lane's part of the G query codes (the whole code when a lane owns whole keys)
+        uint32_t qc[G][CWL];
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int w = 0; w < W; ++w) qc[g][w] = a.qcode[(bh0 + g) * W + w];
+            for (int w = 0; w < CWL; ++w) qc[g][w] = a.qcode[(bh0 + g) * W + sub * CWL + w];
 
-        // distances of this thread's 16 keys, two per register; key slot i sits at block offset i*256 + tid
+        // distances of the 16 keys this lane owns, two per register
         uint32_t dv[G][kKPT / 2];
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
             for (int i = 0; i < kKPT / 2; ++i) dv[g][i] = 0xffffffffu;
 
+        // A "slot" is one load instruction of the workgroup: KPS = 256 / LPK keys, LPK adjacent lanes
+        // per key, 16 bytes per lane (fully coalesced).  The partial distances of a key are added
+        // across its LPK lanes; lane `sub` of the key keeps the slots with s % LPK == sub, so every
+        // lane ends up owning 16 keys: key j of a lane is slot j * LPK + sub, token offset
+        // (j * LPK + sub) * KPS + kq.
 #pragma unroll
-        for (int bt = 0; bt < kKPT / KB; ++bt) {
-            uint32_t kw[KB][W];
+        for (int bt = 0; bt < SLOTS / KB; ++bt) {
+            uint32_t kw[KB][CWL];
 #pragma unroll
             for (int u = 0; u < KB; ++u) {
-                const int i = bt * KB + u;
-                if (i * kThreads + tid < n_blk) load_key<W>(base + static_cast<size_t>(i) * (kThreads * W * 4), lane_off, kw[u]);
+                const int sl = bt * KB + u;
+                if (sl * KPS + kq < n_blk) load_key<CWL>(base + static_cast<size_t>(sl) * (kThreads * CWL * 4), lane_off, kw[u]);
             }
 #pragma unroll
             for (int u = 0; u < KB; ++u) {
-                const int i = bt * KB + u;
-                if (i * kThreads + tid < n_blk) {
+                const int sl = bt * KB + u;
+                const bool valid = sl * KPS + kq < n_blk;
 #pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        uint32_t d = 0;
+                for (int g = 0; g < G; ++g) {
+                    uint32_t d = 0;
 #pragma unroll
-                        for (int w = 0; w < W; ++w) d += popc(kw[u][w] ^ qc[g][w]);
+                    for (int w = 0; w < CWL; ++w) d += popc(kw[u][w] ^ qc[g][w]);
+#pragma unroll
+                    for (int off = 1; off < LPK; off <<= 1) d += __shfl_xor(d, off);
+                    if (valid && (LPK == 1 || sub == sl % LPK)) {
+                        const int j = sl / LPK;   // index among the keys this lane owns
                         atomicAdd(&hist[(g * BINS + d) * R + rep], 1u);
-                        if (i & 1) dv[g][i >> 1] = (dv[g][i >> 1] & 0x0000ffffu) | (d << 16);
-                        else dv[g][i >> 1] = (dv[g][i >> 1] & 0xffff0000u) | d;
+                        if (j & 1) dv[g][j >> 1] = (dv[g][j >> 1] & 0x0000ffffu) | (d << 16);
+                        else dv[g][j >> 1] = (dv[g][j >> 1] & 0xffff0000u) | d;
                     }
                 }
             }
@@ -222,7 +238,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
                 const unsigned long long m = __ballot(p);
                 if (p) {
                     const uint32_t at = run + __builtin_popcountll(m & ((1ull << lane) - 1ull));
-                    if (at < static_cast<uint32_t>(kWaveCap)) cl[at] = (d << 16) | static_cast<uint32_t>(i * kThreads + tid);
+                    if (at < static_cast<uint32_t>(kWaveCap)) cl[at] = (d << 16) | static_cast<uint32_t>((i * LPK + sub) * KPS + kq);
                 }
                 run += __builtin_popcountll(m);
             }
@@ -280,7 +296,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     for (int bin = tid; bin < BINS; bin += kSelThreads) {
         const uint32_t c = gc[bin];
         const uint32_t p = bin ? gc[bin - 1] : 0u;
-        if (c >= static_cast<uint32_t>(k) && p < static_cast<uint32_t>(k)) { s_T = bin; s_r = static_cast<uint32_t>(k) - p; }
+        // exactly one bin qualifies for a consistent histogram; the last bin also takes the case "never
+        // reaches k", so T is a valid bin whatever the workspace holds
+        if ((c >= static_cast<uint32_t>(k) || bin == BINS - 1) && p < static_cast<uint32_t>(k)) {
+            s_T = bin;
+            s_r = static_cast<uint32_t>(k) - p;
+        }
     }
     __syncthreads();
     const uint32_t T = s_T, r = s_r;
@@ -320,7 +341,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
             for (int h = 0; h < PER; ++h) {
                 if (h * kSelThreads + tid < static_cast<int>(meta.count[s])) {
-                    const uint32_t d = ce[s][h] >> 16, off = ce[s][h] & 0xffffu;
+                    const uint32_t d = ce[s][h] >> 16, off = ce[s][h] & (kTPB - 1);
                     if (d < T) atomicOr(&lt_bits[off >> 5], 1u << (off & 31));
                     else if (d == T) atomicOr(&eq_bits[off >> 5], 1u << (off & 31));
                 }
