@@ -92,6 +92,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
     constexpr int SLOTS = kKPT * LPK;      // load instructions per thread and task
     constexpr int KPS = kThreads / LPK;    // keys per slot
     constexpr int KB = CWL <= 4 ? 4 : (CWL <= 8 ? 2 : 1);  // loads in flight per lane
+    constexpr bool PF = G <= 2;            // fetch a task's first loads ahead (costs KB * CWL registers)
     __shared__ uint32_t hist[G * BINS * R];
     __shared__ uint32_t cum[G * BINS];     // this block's histogram, then its cumulative form
     __shared__ uint32_t gacc[G * BINS];    // cumulative histogram summed over this run of tasks
@@ -109,6 +110,21 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
 
     const int task0 = blockIdx.x * a.tasks_per_group;
     const int task1 = min(a.total_tasks, task0 + a.tasks_per_group);
+
+    // the first KB loads of a task are issued ahead of time: before the loop for the first task,
+    // before the epilogue of the task in front of it for the others
+    uint32_t pre[KB][CWL];
+    auto fetch_first = [&](int t) {
+        const int bk = t / a.nblk, blk = t % a.nblk;
+        const int64_t t_begin = static_cast<int64_t>(blk) * kTPB;
+        const int n_blk = static_cast<int>(min(static_cast<int64_t>(kTPB), a.n_tokens - t_begin));
+        const char* base = reinterpret_cast<const char*>(a.codes + (static_cast<int64_t>(bk) * a.Nmax + t_begin) * W);
+#pragma unroll
+        for (int u = 0; u < KB; ++u)
+            if (u * KPS + kq < n_blk) load_key<CWL>(base + static_cast<size_t>(u) * (kThreads * CWL * 4), lane_off, pre[u]);
+    };
+    if (PF && task0 < task1) fetch_first(task0);
+
     for (int task = task0; task < task1; ++task) {
         const int bk = task / a.nblk, blk = task % a.nblk;
         const int b = bk / a.Hkv, hk = bk % a.Hkv;
@@ -139,11 +155,19 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
 #pragma unroll
         for (int bt = 0; bt < SLOTS / KB; ++bt) {
             uint32_t kw[KB][CWL];
+            if (PF && bt == 0) {   // fetched before the previous task's epilogue (or before the loop)
 #pragma unroll
-            for (int u = 0; u < KB; ++u) {
-                const int sl = bt * KB + u;
-                if (sl * KPS + kq < n_blk) load_key<CWL>(base + static_cast<size_t>(sl) * (kThreads * CWL * 4), lane_off, kw[u]);
+                for (int u = 0; u < KB; ++u)
+#pragma unroll
+                    for (int w = 0; w < CWL; ++w) kw[u][w] = pre[u][w];
+            } else {
+#pragma unroll
+                for (int u = 0; u < KB; ++u) {
+                    const int sl = bt * KB + u;
+                    if (sl * KPS + kq < n_blk) load_key<CWL>(base + static_cast<size_t>(sl) * (kThreads * CWL * 4), lane_off, kw[u]);
+                }
             }
+            if (PF && bt == SLOTS / KB - 1 && task + 1 < task1) fetch_first(task + 1);   // in flight during the epilogue
 #pragma unroll
             for (int u = 0; u < KB; ++u) {
                 const int sl = bt * KB + u;
@@ -438,10 +462,10 @@ int launch_score_wg(spotlight_ctx* ctx, const RetrieveArgs& a)
 {
     const Plan& p = ctx->plan;
     constexpr int BINS = W * 32 + 1;
-    // histogram replicas: as many as fit in 32 KB of LDS, at most 32
+    // histogram replicas: 8 if they fit in 32 KB of LDS (more did not make the LDS atomics faster
+    // and make the per-block fold and re-zero slower), fewer for wide codes and big groups
     constexpr int kCap = 32768;
-    constexpr int R = (G * BINS * 32 * 4 <= kCap) ? 32 : (G * BINS * 16 * 4 <= kCap) ? 16
-                    : (G * BINS * 8 * 4 <= kCap) ? 8 : (G * BINS * 4 * 4 <= kCap) ? 4
+    constexpr int R = (G * BINS * 8 * 4 <= kCap) ? 8 : (G * BINS * 4 * 4 <= kCap) ? 4
                     : (G * BINS * 2 * 4 <= kCap) ? 2 : 1;
     auto kern = score_kernel<W, G, R>;
     // persistent grid: as many workgroups as the chip holds at once
