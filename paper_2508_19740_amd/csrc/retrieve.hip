@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
     __shared__ uint32_t s_thi[G];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int rep = tid & (R - 1);
+    const int rep = (tid / LPK) & (R - 1);   // the lanes of one key never record the same slot
     const int Hq = a.Hkv * G;
     const uint32_t lane_off = static_cast<uint32_t>(tid) * (CWL * 4);
     const int sub = tid % LPK, kq = tid / LPK;   // part of the key this lane reads, key within a slot
