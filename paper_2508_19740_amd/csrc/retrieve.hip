@@ -25,6 +25,8 @@
 // token index, with integer arithmetic only: identical bits on every run.
 #include "internal.h"
 
+#include <type_traits>
+
 namespace spotlight {
 namespace {
 
@@ -64,6 +66,19 @@ __device__ __forceinline__ void load_key(const char* __restrict__ base, uint32_t
     }
 }
 
+// Sum of x over the LPK (1, 2 or 4) adjacent lanes that share a key: data-parallel-primitive moves
+// within a group of four lanes, no LDS traffic.
+template <int LPK>
+__device__ __forceinline__ uint32_t add_across_key(uint32_t x)
+{
+    if constexpr (LPK >= 2)   // lanes 1 0 3 2
+        x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0xB1, 0xf, 0xf, true));
+    if constexpr (LPK >= 4)   // lanes 2 3 0 1
+        x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x4E, 0xf, 0xf, true));
+    static_assert(LPK == 1 || LPK == 2 || LPK == 4, "a key spans at most four lanes");
+    return x;
+}
+
 // ------------------------------------------------------------------------------------ score
 struct ScoreArgs {
     const uint32_t* codes;
@@ -92,7 +107,6 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
     constexpr int SLOTS = kKPT * LPK;      // load instructions per thread and task
     constexpr int KPS = kThreads / LPK;    // keys per slot
     constexpr int KB = CWL <= 4 ? 4 : (CWL <= 8 ? 2 : 1);  // loads in flight per lane
-    constexpr bool PF = G <= 2;            // fetch a task's first loads ahead (costs KB * CWL registers)
     __shared__ uint32_t hist[G * BINS * R];
     __shared__ uint32_t cum[G * BINS];     // this block's histogram, then its cumulative form
     __shared__ uint32_t gacc[G * BINS];    // cumulative histogram summed over this run of tasks
@@ -111,19 +125,28 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
     const int task0 = blockIdx.x * a.tasks_per_group;
     const int task1 = min(a.total_tasks, task0 + a.tasks_per_group);
 
-    // the first KB loads of a task are issued ahead of time: before the loop for the first task,
-    // before the epilogue of the task in front of it for the others
-    uint32_t pre[KB][CWL];
-    auto fetch_first = [&](int t) {
+    // Loads run one batch (KB slots) ahead of the arithmetic, in two register buffers that swap
+    // roles; the first batch of a task is fetched during the epilogue of the task in front of it
+    // and is always in buf[0] (the number of batches is even).  Full blocks load unpredicated.
+    // Groups of eight heads keep too many distances in registers for a second buffer: they load
+    // each batch right before using it.
+    constexpr int NB = SLOTS / KB;
+    constexpr bool AHEAD = G <= 4;
+    static_assert(NB % 2 == 0, "the first batch of every task lands in buf[0]");
+    uint32_t buf[AHEAD ? 2 : 1][KB][CWL];
+    auto fetch = [&](auto full, int t, int bt, uint32_t (&dst)[KB][CWL]) {
         const int bk = t / a.nblk, blk = t % a.nblk;
         const int64_t t_begin = static_cast<int64_t>(blk) * kTPB;
         const int n_blk = static_cast<int>(min(static_cast<int64_t>(kTPB), a.n_tokens - t_begin));
         const char* base = reinterpret_cast<const char*>(a.codes + (static_cast<int64_t>(bk) * a.Nmax + t_begin) * W);
 #pragma unroll
-        for (int u = 0; u < KB; ++u)
-            if (u * KPS + kq < n_blk) load_key<CWL>(base + static_cast<size_t>(u) * (kThreads * CWL * 4), lane_off, pre[u]);
+        for (int u = 0; u < KB; ++u) {
+            const int sl = bt * KB + u;
+            if (decltype(full)::value || sl * KPS + kq < n_blk)
+                load_key<CWL>(base + static_cast<size_t>(sl) * (kThreads * CWL * 4), lane_off, dst[u]);
+        }
     };
-    if (PF && task0 < task1) fetch_first(task0);
+    if (AHEAD && task0 < task1) fetch(std::false_type{}, task0, 0, buf[0]);
 
     for (int task = task0; task < task1; ++task) {
         const int bk = task / a.nblk, blk = task % a.nblk;
@@ -131,8 +154,6 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
         const int64_t bh0 = static_cast<int64_t>(b) * Hq + hk * G;  // first query head of the group
         const int64_t t_begin = static_cast<int64_t>(blk) * kTPB;
         const int n_blk = static_cast<int>(min(static_cast<int64_t>(kTPB), a.n_tokens - t_begin));
-        const char* base = reinterpret_cast<const char*>(a.codes + (static_cast<int64_t>(bk) * a.Nmax + t_begin) * W);
-
         // this lane's part of the G query codes (the whole code when a lane owns whole keys)
         uint32_t qc[G][CWL];
 #pragma unroll
@@ -152,42 +173,39 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
         // across its LPK lanes; lane `sub` of the key keeps the slots with s % LPK == sub, so every
         // lane ends up owning 16 keys: key j of a lane is slot j * LPK + sub, token offset
         // (j * LPK + sub) * KPS + kq.
+        auto score_block = [&](auto full) {
 #pragma unroll
-        for (int bt = 0; bt < SLOTS / KB; ++bt) {
-            uint32_t kw[KB][CWL];
-            if (PF && bt == 0) {   // fetched before the previous task's epilogue (or before the loop)
-#pragma unroll
-                for (int u = 0; u < KB; ++u)
-#pragma unroll
-                    for (int w = 0; w < CWL; ++w) kw[u][w] = pre[u][w];
-            } else {
-#pragma unroll
-                for (int u = 0; u < KB; ++u) {
-                    const int sl = bt * KB + u;
-                    if (sl * KPS + kq < n_blk) load_key<CWL>(base + static_cast<size_t>(sl) * (kThreads * CWL * 4), lane_off, kw[u]);
-                }
-            }
-            if (PF && bt == SLOTS / KB - 1 && task + 1 < task1) fetch_first(task + 1);   // in flight during the epilogue
+        for (int bt = 0; bt < NB; ++bt) {
+            uint32_t (&kw)[KB][CWL] = buf[AHEAD ? bt & 1 : 0];
+            if constexpr (!AHEAD) fetch(full, task, bt, buf[0]);
+            else if (bt + 1 < NB) fetch(full, task, bt + 1, buf[(bt + 1) & 1]);
+            else if (task + 1 < task1) fetch(std::false_type{}, task + 1, 0, buf[0]);   // in flight during the epilogue
 #pragma unroll
             for (int u = 0; u < KB; ++u) {
                 const int sl = bt * KB + u;
-                const bool valid = sl * KPS + kq < n_blk;
+                const bool valid = decltype(full)::value || sl * KPS + kq < n_blk;
+                uint32_t d[G];
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
-                    uint32_t d = 0;
+                    d[g] = 0;
 #pragma unroll
-                    for (int w = 0; w < CWL; ++w) d += popc(kw[u][w] ^ qc[g][w]);
+                    for (int w = 0; w < CWL; ++w) d[g] += popc(kw[u][w] ^ qc[g][w]);
+                    d[g] = add_across_key<LPK>(d[g]);
+                }
+                if (valid && (LPK == 1 || sub == sl % LPK)) {
+                    const int j = sl / LPK;   // index among the keys this lane owns
 #pragma unroll
-                    for (int off = 1; off < LPK; off <<= 1) d += __shfl_xor(d, off);
-                    if (valid && (LPK == 1 || sub == sl % LPK)) {
-                        const int j = sl / LPK;   // index among the keys this lane owns
-                        atomicAdd(&hist[(g * BINS + d) * R + rep], 1u);
-                        if (j & 1) dv[g][j >> 1] = (dv[g][j >> 1] & 0x0000ffffu) | (d << 16);
-                        else dv[g][j >> 1] = (dv[g][j >> 1] & 0xffff0000u) | d;
+                    for (int g = 0; g < G; ++g) {
+                        atomicAdd(&hist[(g * BINS + d[g]) * R + rep], 1u);
+                        if (j & 1) dv[g][j >> 1] = (dv[g][j >> 1] & 0x0000ffffu) | (d[g] << 16);
+                        else dv[g][j >> 1] = (dv[g][j >> 1] & 0xffff0000u) | d[g];
                     }
                 }
             }
         }
+        };
+        if (n_blk == kTPB) score_block(std::true_type{});
+        else score_block(std::false_type{});
         __syncthreads();
 
         // fold the replicas (rotated so that neighbouring threads hit different banks)
