@@ -35,6 +35,31 @@ struct Plan {
     size_t total_bytes;
 };
 
+#if defined(__HIPCC__)
+// Inclusive prefix sum of x over the 64 lanes of a wavefront, by data-parallel-primitive moves
+// (shifts within rows of 16 lanes, then the last lane of a row broadcast to the rows behind it):
+// six dependent vector instructions, no LDS round trips.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x)
+{
+#define SPOTLIGHT_DPP_ADD(ctrl, rows) \
+    x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), ctrl, rows, 0xf, true))
+    SPOTLIGHT_DPP_ADD(0x111, 0xf);   // row_shr:1
+    SPOTLIGHT_DPP_ADD(0x112, 0xf);   // row_shr:2
+    SPOTLIGHT_DPP_ADD(0x114, 0xf);   // row_shr:4
+    SPOTLIGHT_DPP_ADD(0x118, 0xf);   // row_shr:8
+    SPOTLIGHT_DPP_ADD(0x142, 0xa);   // lane 15 of rows 0 and 2 to rows 1 and 3
+    SPOTLIGHT_DPP_ADD(0x143, 0xc);   // lane 31 to rows 2 and 3
+#undef SPOTLIGHT_DPP_ADD
+    return x;
+}
+
+// Sum of x over the wavefront, in every lane.
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x)
+{
+    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(wave_inclusive_scan(x)), 63));
+}
+#endif
+
 int make_plan(const spotlight_config* cfg, Plan* plan);  // SPOTLIGHT_OK or an error code; host only
 
 struct ProfileRec {

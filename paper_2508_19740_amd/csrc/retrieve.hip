@@ -231,13 +231,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
                 tot += bin < BINS ? cum[g * BINS + bin] : 0u;
                 v[c] = tot;
             }
-            uint32_t inc = tot;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const uint32_t up = __shfl_up(inc, off);
-                if (lane >= off) inc += up;
-            }
-            const uint32_t before = inc - tot;
+            const uint32_t before = wave_inclusive_scan(tot) - tot;
             uint32_t prev = before;
 #pragma unroll
             for (int c = 0; c < CH; ++c) {
@@ -319,15 +313,18 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const uint32_t* gc = gcum + bh * BINS;
     const uint32_t* bc = blockcum + bh * max_blocks * BINS;
     const int64_t slot = bh * max_blocks + blk;
-    const BlockMeta meta = blockmeta[slot];
-
-    // the candidate entries are fetched before the threshold is known, so that their latency
-    // overlaps the threshold search
+    // The candidate entries are fetched before the threshold is known, so that their latency
+    // overlaps the threshold search; the first half of every sub-list (which is all of it unless
+    // the block is unusually dense) even before the sub-list lengths are known.  Entries past a
+    // sub-list's length hold whatever the workspace held: they are never looked at.
     uint32_t ce[SUB][PER];
+#pragma unroll
+    for (int s = 0; s < SUB; ++s) ce[s][0] = cand[(slot * SUB + s) * kWaveCap + tid];
+    const BlockMeta meta = blockmeta[slot];
 #pragma unroll
     for (int s = 0; s < SUB; ++s)
 #pragma unroll
-        for (int h = 0; h < PER; ++h) {
+        for (int h = 1; h < PER; ++h) {
             ce[s][h] = 0;
             if (meta.count[s] != kWaveFull && h * kSelThreads + tid < static_cast<int>(meta.count[s]))
                 ce[s][h] = cand[(slot * SUB + s) * kWaveCap + h * kSelThreads + tid];
@@ -356,8 +353,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         lt += l;
         eq += le - l;
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) { lt += __shfl_xor(lt, off); eq += __shfl_xor(eq, off); }
+    lt = wave_sum(lt);
+    eq = wave_sum(eq);
     if (lane == 0) { red[0][wave] = lt; red[1][wave] = eq; }
     __syncthreads();
     lt = red[0][0] + red[0][1];
@@ -412,12 +409,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const uint32_t lw = lt_bits[tid];
     uint32_t ew = eq_bits[tid];
     const uint32_t ecount = popc(ew);
-    uint32_t sc = ecount;  // inclusive scan of tie counts over threads (token order)
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t up = __shfl_up(sc, off);
-        if (lane >= off) sc += up;
-    }
+    const uint32_t sc = wave_inclusive_scan(ecount);  // tie counts over threads (token order)
     if (lane == 63) wsum[wave] = sc;
     __syncthreads();
     uint32_t eq_before = sc - ecount;
@@ -428,12 +420,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     uint32_t sel = lw | ew;
     const uint32_t cnt = popc(sel);
     __syncthreads();  // wsum is reused
-    uint32_t sn = cnt;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t up = __shfl_up(sn, off);
-        if (lane >= off) sn += up;
-    }
+    const uint32_t sn = wave_inclusive_scan(cnt);
     if (lane == 63) wsum[wave] = sn;
     __syncthreads();
     pos += sn - cnt;
