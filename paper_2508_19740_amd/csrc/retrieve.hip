@@ -106,7 +106,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
     constexpr int CWL = W / LPK;           // code words per lane
     constexpr int SLOTS = kKPT * LPK;      // load instructions per thread and task
     constexpr int KPS = kThreads / LPK;    // keys per slot
-    constexpr int KB = CWL <= 4 ? 4 : (CWL <= 8 ? 2 : 1);  // loads in flight per lane
+    constexpr int KB = CWL <= 4 ? 4 : (CWL <= 8 ? 2 : 1);  // slots per batch of loads
     __shared__ uint32_t hist[G * BINS * R];
     __shared__ uint32_t cum[G * BINS];     // this block's histogram, then its cumulative form
     __shared__ uint32_t gacc[G * BINS];    // cumulative histogram summed over this run of tasks
@@ -128,10 +128,10 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
     // Loads run one batch (KB slots) ahead of the arithmetic, in two register buffers that swap
     // roles; the first batch of a task is fetched during the epilogue of the task in front of it
     // and is always in buf[0] (the number of batches is even).  Full blocks load unpredicated.
-    // Groups of eight heads keep too many distances in registers for a second buffer: they load
-    // each batch right before using it.
+    // Groups of four or eight heads keep too many distances in registers for a second buffer (it
+    // measured slower): they load each batch right before using it.
     constexpr int NB = SLOTS / KB;
-    constexpr bool AHEAD = G <= 4;
+    constexpr bool AHEAD = G <= 2;
     static_assert(NB % 2 == 0, "the first batch of every task lands in buf[0]");
     uint32_t buf[AHEAD ? 2 : 1][KB][CWL];
     auto fetch = [&](auto full, int t, int bt, uint32_t (&dst)[KB][CWL]) {
@@ -197,8 +197,12 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
                         atomicAdd(&hist[(g * BINS + d[g]) * R + rep], 1u);
-                        if (j & 1) dv[g][j >> 1] = (dv[g][j >> 1] & 0x0000ffffu) | (d[g] << 16);
-                        else dv[g][j >> 1] = (dv[g][j >> 1] & 0xffff0000u) | d[g];
+                        if constexpr (decltype(full)::value) {   // both halves get written: no mask needed
+                            dv[g][j >> 1] = (j & 1) ? (d[g] << 16) | dv[g][j >> 1] : d[g];
+                        } else {
+                            if (j & 1) dv[g][j >> 1] = (dv[g][j >> 1] & 0x0000ffffu) | (d[g] << 16);
+                            else dv[g][j >> 1] = (dv[g][j >> 1] & 0xffff0000u) | d[g];
+                        }
                     }
                 }
             }
