@@ -41,6 +41,9 @@ def lib():
         L.ref_retrieve_topk.argtypes = [i32, i32, i32, i32, i32, i32, i64, i32, i32, vp, vp, vp, vp,
                                         vp, i64, i32, vp, vp, vp]
         L.ref_sparse_decode.argtypes = [i32, i32, i32, i32, i64, i32, vp, vp, vp, vp, i32, f64, vp]
+        L.ref_topk_forced.argtypes = [vp, i64, i32, i32, i32, vp]
+        L.ref_decode_step.argtypes = [i32, i32, i32, i32, i32, i32, i64, i32, i32, vp, vp, vp, vp, vp, vp,
+                                      vp, i64, i32, i32, i32, f64, vp, vp]
         _lib = L
     return _lib
 
@@ -125,6 +128,13 @@ def topk(dist: torch.Tensor, k: int) -> torch.Tensor:
     return idx
 
 
+def topk_forced(dist: torch.Tensor, k: int, n_sink: int, n_local: int) -> torch.Tensor:
+    """The first n_sink and last n_local tokens plus the nearest of the others, k in all, ascending."""
+    idx = torch.empty(k, dtype=torch.int32)
+    _check(lib().ref_topk_forced(_p(dist), dist.numel(), k, n_sink, n_local, _p(idx)), "topk_forced")
+    return idx
+
+
 def sparse_attention(q, K, V, idx, scale: float) -> torch.Tensor:
     """q [d]; K, V [n, d] of one head; idx [k] int32 -> out [d] float32."""
     d = q.numel()
@@ -168,3 +178,17 @@ def sparse_decode(q, K, V, idx, scale: float) -> torch.Tensor:
     _check(lib().ref_sparse_decode(B, Hq, Hkv, d, Nmax, _dt(K), _p(q), _p(K), _p(V), _p(idx), k,
                                    float(scale), _p(out)), "sparse_decode")
     return out
+
+
+def decode_step(q, K, V, w1, b1, w2, codes, n_tokens: int, k: int, n_sink: int, n_local: int, scale: float):
+    """One decode step: hash K[:, :, n_tokens-1] into codes (in place), retrieve with forced sink /
+    local tokens, attend.  Returns idx [B, Hq, k] int32 and out [B, Hq, d] float32."""
+    B, Hq, d = q.shape
+    _, Hkv, Nmax, W = codes.shape
+    hidden = 0 if w2 is None else w1.shape[1]
+    idx = torch.empty(B, Hq, k, dtype=torch.int32)
+    out = torch.empty(B, Hq, d, dtype=torch.float32)
+    _check(lib().ref_decode_step(B, Hq, Hkv, d, W * 32, hidden, Nmax, _dt(K), _dt(w1), _p(q), _p(K), _p(V),
+                                 _p(w1), _p(b1), _p(w2), _p(codes), n_tokens, k, n_sink, n_local,
+                                 float(scale), _p(idx), _p(out)), "decode_step")
+    return idx, out

@@ -287,6 +287,33 @@ int ref_topk(const uint16_t *dist, int64_t n, int k, int32_t *idx)
     return REF_OK;
 }
 
+/* Top-k with forced tokens: the configuration columns "Sink" and "Local" of the perplexity
+ * comparison with MagicPIG (first n_sink tokens, last n_local tokens always kept); the current
+ * token that Eq. 1 concatenates is the local window of one.  With
+ *   F = { t < n_sink }  U  { t >= n - n_local },
+ * the result is F together with the k - |F| nearest of the OTHER tokens (distance, then token
+ * index), in increasing token order: k indices in all.  Needs |F| <= k. */
+int ref_topk_forced(const uint16_t *dist, int64_t n, int k, int n_sink, int n_local, int32_t *idx)
+{
+    if (!dist || !idx || n <= 0 || k <= 0 || k > n || n > INT32_MAX || n_sink < 0 || n_local < 0) return REF_EINVAL;
+    int64_t n_forced = 0;
+    for (int64_t t = 0; t < n; ++t) n_forced += (t < n_sink || t >= n - n_local);
+    if (n_forced > k) return REF_EINVAL;
+    ref_pair *p = (ref_pair *)malloc(sizeof(ref_pair) * (size_t)n);
+    if (!p) return REF_ENOMEM;
+    int kept = 0;
+    int64_t others = 0;
+    for (int64_t t = 0; t < n; ++t) {
+        if (t < n_sink || t >= n - n_local) idx[kept++] = (int32_t)t;
+        else { p[others].d = dist[t]; p[others].t = (int32_t)t; ++others; }
+    }
+    qsort(p, (size_t)others, sizeof(ref_pair), ref_cmp_pair);
+    for (int i = 0; kept < k; ++i) idx[kept++] = p[i].t;
+    qsort(idx, (size_t)k, sizeof(int32_t), ref_cmp_i32);
+    free(p);
+    return REF_OK;
+}
+
 /* Attention over exactly the rows listed in idx (Eq. 2 then Eq. 1 without the current-token
  * concatenation): s_i = scale * <q, K[idx_i]>, p = softmax(s), out = sum_i p_i V[idx_i].
  * K and V point at one head's [*, d] rows; all sums in fp64; out rounded to binary32. */
@@ -344,11 +371,11 @@ int ref_hash_keys(int B, int Hkv, int d, int L, int hidden, int64_t Nmax, int kv
     return REF_OK;
 }
 
-int ref_retrieve_topk(int B, int Hq, int Hkv, int d, int L, int hidden, int64_t Nmax,
-                      int kv_dtype, int w_dtype, const void *q,
-                      const void *w1, const void *b1, const void *w2,
-                      const uint32_t *codes, int64_t n_tokens, int k,
-                      int32_t *out_idx, uint32_t *out_qcode, uint16_t *out_dist)
+static int ref_retrieve(int B, int Hq, int Hkv, int d, int L, int hidden, int64_t Nmax,
+                        int kv_dtype, int w_dtype, const void *q,
+                        const void *w1, const void *b1, const void *w2,
+                        const uint32_t *codes, int64_t n_tokens, int k, int forced, int n_sink, int n_local,
+                        int32_t *out_idx, uint32_t *out_qcode, uint16_t *out_dist)
 {
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || !q || !codes || !out_idx) return REF_EINVAL;
     if (n_tokens <= 0 || n_tokens > Nmax || k <= 0 || k > n_tokens || L <= 0 || L % 32) return REF_EINVAL;
@@ -373,10 +400,21 @@ int ref_retrieve_topk(int B, int Hq, int Hkv, int d, int L, int hidden, int64_t 
             rc = ref_hamming(qcode, codes + ((int64_t)b * Hkv + hk) * Nmax * W, n_tokens, L, dist);
             if (rc) break;
             if (out_dist) memcpy(out_dist + bh * n_tokens, dist, sizeof(uint16_t) * (size_t)n_tokens);
-            rc = ref_topk(dist, n_tokens, k, out_idx + bh * k);
+            rc = forced ? ref_topk_forced(dist, n_tokens, k, n_sink, n_local, out_idx + bh * k)
+                        : ref_topk(dist, n_tokens, k, out_idx + bh * k);
         }
     free(dist);
     return rc;
+}
+
+int ref_retrieve_topk(int B, int Hq, int Hkv, int d, int L, int hidden, int64_t Nmax,
+                      int kv_dtype, int w_dtype, const void *q,
+                      const void *w1, const void *b1, const void *w2,
+                      const uint32_t *codes, int64_t n_tokens, int k,
+                      int32_t *out_idx, uint32_t *out_qcode, uint16_t *out_dist)
+{
+    return ref_retrieve(B, Hq, Hkv, d, L, hidden, Nmax, kv_dtype, w_dtype, q, w1, b1, w2, codes, n_tokens, k,
+                        0, 0, 0, out_idx, out_qcode, out_dist);
 }
 
 int ref_sparse_decode(int B, int Hq, int Hkv, int d, int64_t Nmax, int kv_dtype,
@@ -399,4 +437,23 @@ int ref_sparse_decode(int B, int Hq, int Hkv, int d, int64_t Nmax, int kv_dtype,
         }
     }
     return rc_all;
+}
+
+/* One decode step of a layer, in the order the method runs it: the key of the token just appended
+ * (row n_tokens - 1 of K) is hashed into the code cache, the query is hashed and scored against
+ * the n_tokens cached codes, the top-k (with the forced sink / local tokens, see ref_topk_forced)
+ * is taken per query head, and attention runs over exactly those rows.  codes is updated in place. */
+int ref_decode_step(int B, int Hq, int Hkv, int d, int L, int hidden, int64_t Nmax, int kv_dtype, int w_dtype,
+                    const void *q, const void *K, const void *V,
+                    const void *w1, const void *b1, const void *w2,
+                    uint32_t *codes, int64_t n_tokens, int k, int n_sink, int n_local, double scale,
+                    int32_t *out_idx, float *out)
+{
+    if (n_tokens <= 0 || n_tokens > Nmax) return REF_EINVAL;
+    int rc = ref_hash_keys(B, Hkv, d, L, hidden, Nmax, kv_dtype, w_dtype, K, w1, b1, w2, n_tokens - 1, 1, codes);
+    if (rc) return rc;
+    rc = ref_retrieve(B, Hq, Hkv, d, L, hidden, Nmax, kv_dtype, w_dtype, q, w1, b1, w2, codes, n_tokens, k,
+                      1, n_sink, n_local, out_idx, NULL, NULL);
+    if (rc) return rc;
+    return ref_sparse_decode(B, Hq, Hkv, d, Nmax, kv_dtype, q, K, V, out_idx, k, scale, out);
 }
