@@ -164,6 +164,23 @@ def main():
     ctx.profile_enable(False)
     stage_us = {name: (ms * 1e3 / n if n else None) for name, (ms, n) in stage.items()}
 
+    # ------------------------------------------------------------------ the same step as ONE call
+    # spotlight_decode_step: key and query hashed in one launch, then score, select, attend, merge.
+    def fused(i):
+        lay = layers[i % n_layers]
+        n_tok = N + (i // n_layers) % cfg.extra_tokens + 1 if grow else N
+        ctx.decode_step(lay["q"], lay["K"], lay["V"], *lay["weights"], lay["codes"], n_tok, k, 0, 0,
+                        out_idx=lay["idx"], out=lay["out"])
+
+    for i in range(args.warmup):
+        fused(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K_steps):
+        fused(i)
+    torch.cuda.synchronize()
+    fused_ms_per_step = (time.perf_counter() - t0) * 1e3 / K_steps
+
     # ------------------------------------------------------------------ algorithmic bytes
     # score: every key code read once (L/8 bytes per key per key-value head)
     score_bytes = B * Hkv * N * (L // 8)
@@ -244,6 +261,7 @@ def main():
         "retrieve_frac_of_hbm_peak": round(gbps(retrieve_bytes, retrieve_us) / HBM_PEAK_GBPS, 4),
         "attend_gbps": round(gbps(attend_bytes, attend_us), 1),
         "attend_frac_of_hbm_peak": round(gbps(attend_bytes, attend_us) / HBM_PEAK_GBPS, 4),
+        "decode_step_one_call_ms": round(fused_ms_per_step, 4),
         "kernel_us": {kname: (round(v, 2) if v is not None else None) for kname, v in stage_us.items()},
         "bulk_hash_keys_ms_per_layer": round(bulk_ms, 3),
         "bulk_hash_keys_gflops": round(2.0 * B * Hkv * N * (cfg.hidden * d + L * cfg.hidden if cfg.hidden else L * d)

@@ -149,6 +149,34 @@ int spotlight_sparse_decode(spotlight_ctx *ctx, const void *q, const void *K, co
                             const int32_t *idx, int32_t k, float scale, float *out);
 
 /*
+ * One decode step of a layer in one call, in the order the method runs it: the key of the token
+ * just appended (row n_tokens-1 of K) is hashed into the code cache, the queries are hashed
+ * (both in one kernel launch), scored against the n_tokens cached codes and the top-k taken per
+ * query head, and attention runs over the selected rows (Eq. 5-6, Eq. 3, Eq. 2, Eq. 1).
+ *
+ * Forced tokens: the first n_sink and the last n_local tokens of the cache are always selected
+ * (the "Sink (4)" and "Local (64)" columns of the paper's perplexity comparison with MagicPIG);
+ * the remaining k - |forced| places go to the nearest of the OTHER tokens, ties to the lower
+ * index.  n_local >= 1 attends the current token as Eq. 1's concatenation does.  n_sink = n_local
+ * = 0 gives exactly spotlight_hash_keys(t0 = n_tokens-1, n_new = 1) + spotlight_retrieve_topk +
+ * spotlight_sparse_decode.
+ *
+ *   q        [B, Hq, d]         kv_dtype
+ *   K, V     [B, Hkv, Nmax, d]  kv_dtype   rows 0 .. n_tokens-1 valid, row n_tokens-1 the new token
+ *   codes    [B, Hkv, Nmax, W]  uint32     row n_tokens-1 is written, rows 0 .. n_tokens-1 are read
+ *   out_idx  [B, Hq, k]         int32      selected token indices in increasing order
+ *   out      [B, Hq, d]         float32
+ * The call enqueues five kernels on the context's stream and nothing else (no allocation, no
+ * memset, no copy), so it can be captured into a HIP graph.
+ * Errors: INVALID_ARG unless 1 <= n_tokens <= Nmax, 1 <= k <= min(n_tokens, max_topk),
+ * n_sink >= 0, n_local >= 0 and the number of forced tokens is at most k.
+ */
+int spotlight_decode_step(spotlight_ctx *ctx, const void *q, const void *K, const void *V,
+                          const spotlight_hash_weights *w, uint32_t *codes, int64_t n_tokens,
+                          int32_t k, int32_t n_sink, int32_t n_local, float scale,
+                          int32_t *out_idx, float *out);
+
+/*
  * Stage timing for benchmarks.  While enabled, every kernel launch is bracketed by two HIP events
  * on the context's stream.  spotlight_profile_read waits for the stream, adds the elapsed times of
  * the launches recorded since the last read to the per-stage totals and returns the totals for

@@ -22,7 +22,7 @@ STAGES = ("hash_keys", "hash_query", "score", "select", "attend")
 SYMBOLS = (
     "spotlight_validate_config", "spotlight_workspace_bytes", "spotlight_create", "spotlight_destroy",
     "spotlight_set_stream", "spotlight_strerror", "spotlight_hash_keys", "spotlight_retrieve_topk",
-    "spotlight_sparse_decode", "spotlight_profile_enable", "spotlight_profile_read",
+    "spotlight_sparse_decode", "spotlight_decode_step", "spotlight_profile_enable", "spotlight_profile_read",
 )
 
 
@@ -57,6 +57,8 @@ def _load() -> C.CDLL:
     lib.spotlight_hash_keys.argtypes = [vp, vp, C.POINTER(HashWeights), i64, i64, vp]
     lib.spotlight_retrieve_topk.argtypes = [vp, vp, C.POINTER(HashWeights), vp, i64, i32, vp, vp, vp]
     lib.spotlight_sparse_decode.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, vp]
+    lib.spotlight_decode_step.argtypes = [vp, vp, vp, vp, C.POINTER(HashWeights), vp, i64, i32, i32, i32,
+                                          C.c_float, vp, vp]
     lib.spotlight_profile_enable.argtypes = [vp, C.c_int]
     lib.spotlight_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
     return lib
@@ -202,6 +204,32 @@ class Spotlight:
             raise SpotlightError(rc, "spotlight_sparse_decode")
         return out
 
+    def decode_step(self, q, K, V, w1, b1, w2, codes, n_tokens: int, k: int, n_sink: int = 0, n_local: int = 0,
+                    scale: Optional[float] = None, out_idx=None, out=None):
+        """Hash the key at row n_tokens-1 into codes, retrieve (first n_sink / last n_local tokens
+        forced), attend: one C call, five kernel launches.  Returns (idx, out)."""
+        self._sync_stream()
+        qp = self._chk(q, (self.B, self.Hq, self.d), self.kv_dtype, "q")
+        kp = self._chk(K, (self.B, self.Hkv, self.Nmax, self.d), self.kv_dtype, "K")
+        vp = self._chk(V, (self.B, self.Hkv, self.Nmax, self.d), self.kv_dtype, "V")
+        cp = self._chk(codes, (self.B, self.Hkv, self.Nmax, self.W), torch.int32, "codes")
+        w = self._weights(w1, b1, w2)
+        if not all(isinstance(v, int) for v in (k, n_tokens, n_sink, n_local)):
+            raise TypeError("k, n_tokens, n_sink and n_local are ints")
+        if out_idx is None:
+            out_idx = torch.empty(self.B, self.Hq, max(k, 0), dtype=torch.int32, device=self.device)
+        ip = self._chk(out_idx, (self.B, self.Hq, k), torch.int32, "out_idx")
+        if out is None:
+            out = torch.empty(self.B, self.Hq, self.d, dtype=torch.float32, device=self.device)
+        op = self._chk(out, (self.B, self.Hq, self.d), torch.float32, "out")
+        if scale is None:
+            scale = 1.0 / math.sqrt(self.d)
+        rc = lib.spotlight_decode_step(self._h, qp, kp, vp, C.byref(w), cp, n_tokens, k, n_sink, n_local,
+                                       float(scale), ip, op)
+        if rc != OK:
+            raise SpotlightError(rc, "spotlight_decode_step")
+        return out_idx, out
+
     # ------------------------------------------------------------------ stage timing
     def profile_enable(self, on: bool = True):
         rc = lib.spotlight_profile_enable(self._h, 1 if on else 0)
@@ -231,3 +259,7 @@ def spotlight_retrieve_topk(ctx: Spotlight, q, w1, b1, w2, codes, n_tokens, k, *
 
 def spotlight_sparse_decode(ctx: Spotlight, q, K, V, idx, scale=None, out=None):
     return ctx.sparse_decode(q, K, V, idx, scale, out)
+
+
+def spotlight_decode_step(ctx: Spotlight, q, K, V, w1, b1, w2, codes, n_tokens, k, n_sink=0, n_local=0, **kw):
+    return ctx.decode_step(q, K, V, w1, b1, w2, codes, n_tokens, k, n_sink, n_local, **kw)

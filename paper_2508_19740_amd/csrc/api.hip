@@ -43,7 +43,7 @@ int make_plan(const spotlight_config* c, Plan* p)
     p->max_splits = (p->max_topk + kAttendMinRows - 1) / kAttendMinRows;
 
     const size_t BH = static_cast<size_t>(p->B) * p->Hq;
-    const size_t bins = static_cast<size_t>(p->L) + 1;
+    const size_t bins = static_cast<size_t>(p->L) + 2;   // one bin for forced tokens, L + 1 for distances 0 .. L
     size_t off = 0;
     p->off_qcode = off;     off = align_up(off + BH * p->W * 4, 256);
     p->off_gcum = off;      off = align_up(off + BH * bins * 4, 256);
@@ -175,16 +175,11 @@ int spotlight_set_stream(spotlight_ctx* ctx, void* stream)
     return SPOTLIGHT_OK;
 }
 
-int spotlight_hash_keys(spotlight_ctx* ctx, const void* K, const spotlight_hash_weights* w, int64_t t0,
-                        int64_t n_new, uint32_t* codes)
+// The hash job of n_new key rows of every (batch, kv head), written into the code cache.
+static HashLaunch key_job(const spotlight_ctx* ctx, const void* K, const spotlight_hash_weights* w, int64_t t0,
+                          int64_t n_new, uint32_t* codes)
 {
-    if (!ctx || !K || !codes) return SPOTLIGHT_ERR_INVALID_ARG;
     const Plan& p = ctx->plan;
-    int rc = check_weights(ctx, w);
-    if (rc != SPOTLIGHT_OK) return rc;
-    if (t0 < 0 || n_new < 0 || t0 > p.Nmax || n_new > p.Nmax - t0) return SPOTLIGHT_ERR_INVALID_ARG;
-    if (misaligned(K) || misaligned(codes)) return SPOTLIGHT_ERR_INVALID_ARG;
-    if (n_new == 0) return SPOTLIGHT_OK;
     HashLaunch h;
     h.x = K;
     h.x_dtype = p.kv_dtype;
@@ -205,21 +200,14 @@ int spotlight_hash_keys(spotlight_ctx* ctx, const void* K, const spotlight_hash_
     h.code_row0 = t0;
     h.zero = nullptr;
     h.zero_words = 0;
-    return launch_hash(ctx, h, SPOTLIGHT_STAGE_HASH_KEYS);
+    return h;
 }
 
-int spotlight_retrieve_topk(spotlight_ctx* ctx, const void* q, const spotlight_hash_weights* w,
-                            const uint32_t* codes, int64_t n_tokens, int32_t k, int32_t* out_idx,
-                            uint32_t* out_qcode, uint16_t* out_dist)
+// The hash job of the queries, written into the workspace; it also clears the heads' cumulative
+// histograms, which the score kernel adds into.
+static HashLaunch query_job(const spotlight_ctx* ctx, const void* q, const spotlight_hash_weights* w)
 {
-    if (!ctx || !q || !codes || !out_idx) return SPOTLIGHT_ERR_INVALID_ARG;
     const Plan& p = ctx->plan;
-    int rc = check_weights(ctx, w);
-    if (rc != SPOTLIGHT_OK) return rc;
-    if (n_tokens < 1 || n_tokens > p.Nmax) return SPOTLIGHT_ERR_INVALID_ARG;
-    if (k < 1 || k > n_tokens || k > p.max_topk) return SPOTLIGHT_ERR_INVALID_ARG;
-    if (misaligned(q) || misaligned(codes)) return SPOTLIGHT_ERR_INVALID_ARG;
-
     HashLaunch h;
     h.x = q;
     h.x_dtype = p.kv_dtype;
@@ -238,16 +226,67 @@ int spotlight_retrieve_topk(spotlight_ctx* ctx, const void* q, const spotlight_h
     h.codes = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_qcode);
     h.code_head_stride = p.W;
     h.code_row0 = 0;
-    h.zero = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_gcum);  // the score kernel adds into it
-    h.zero_words = p.L + 1;
-    rc = launch_hash(ctx, h, SPOTLIGHT_STAGE_HASH_QUERY);
+    h.zero = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_gcum);
+    h.zero_words = p.L + 2;
+    return h;
+}
+
+int spotlight_hash_keys(spotlight_ctx* ctx, const void* K, const spotlight_hash_weights* w, int64_t t0,
+                        int64_t n_new, uint32_t* codes)
+{
+    if (!ctx || !K || !codes) return SPOTLIGHT_ERR_INVALID_ARG;
+    const Plan& p = ctx->plan;
+    int rc = check_weights(ctx, w);
+    if (rc != SPOTLIGHT_OK) return rc;
+    if (t0 < 0 || n_new < 0 || t0 > p.Nmax || n_new > p.Nmax - t0) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (misaligned(K) || misaligned(codes)) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (n_new == 0) return SPOTLIGHT_OK;
+    return launch_hash(ctx, key_job(ctx, K, w, t0, n_new, codes), SPOTLIGHT_STAGE_HASH_KEYS);
+}
+
+int spotlight_retrieve_topk(spotlight_ctx* ctx, const void* q, const spotlight_hash_weights* w,
+                            const uint32_t* codes, int64_t n_tokens, int32_t k, int32_t* out_idx,
+                            uint32_t* out_qcode, uint16_t* out_dist)
+{
+    if (!ctx || !q || !codes || !out_idx) return SPOTLIGHT_ERR_INVALID_ARG;
+    const Plan& p = ctx->plan;
+    int rc = check_weights(ctx, w);
+    if (rc != SPOTLIGHT_OK) return rc;
+    if (n_tokens < 1 || n_tokens > p.Nmax) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (k < 1 || k > n_tokens || k > p.max_topk) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (misaligned(q) || misaligned(codes)) return SPOTLIGHT_ERR_INVALID_ARG;
+
+    rc = launch_hash(ctx, query_job(ctx, q, w), SPOTLIGHT_STAGE_HASH_QUERY);
     if (rc != SPOTLIGHT_OK) return rc;
     if (out_qcode) {
         if (hipMemcpyAsync(out_qcode, ctx->workspace + p.off_qcode, static_cast<size_t>(p.B) * p.Hq * p.W * 4,
                            hipMemcpyDeviceToDevice, ctx->stream) != hipSuccess)
             return SPOTLIGHT_ERR_HIP;
     }
-    return launch_retrieve(ctx, codes, n_tokens, k, out_idx, out_dist);
+    return launch_retrieve(ctx, codes, n_tokens, k, 0, 0, out_idx, out_dist);
+}
+
+int spotlight_decode_step(spotlight_ctx* ctx, const void* q, const void* K, const void* V,
+                          const spotlight_hash_weights* w, uint32_t* codes, int64_t n_tokens, int32_t k,
+                          int32_t n_sink, int32_t n_local, float scale, int32_t* out_idx, float* out)
+{
+    if (!ctx || !q || !K || !V || !codes || !out_idx || !out) return SPOTLIGHT_ERR_INVALID_ARG;
+    const Plan& p = ctx->plan;
+    int rc = check_weights(ctx, w);
+    if (rc != SPOTLIGHT_OK) return rc;
+    if (n_tokens < 1 || n_tokens > p.Nmax) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (k < 1 || k > n_tokens || k > p.max_topk) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (n_sink < 0 || n_local < 0) return SPOTLIGHT_ERR_INVALID_ARG;
+    const int64_t n_forced = static_cast<int64_t>(n_sink) + n_local >= n_tokens ? n_tokens : static_cast<int64_t>(n_sink) + n_local;
+    if (n_forced > k) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(codes)) return SPOTLIGHT_ERR_INVALID_ARG;
+
+    // queries first: their workgroups also clear the histograms
+    rc = launch_hash_pair(ctx, query_job(ctx, q, w), key_job(ctx, K, w, n_tokens - 1, 1, codes), SPOTLIGHT_STAGE_HASH_QUERY);
+    if (rc != SPOTLIGHT_OK) return rc;
+    rc = launch_retrieve(ctx, codes, n_tokens, k, n_sink, n_local, out_idx, nullptr);
+    if (rc != SPOTLIGHT_OK) return rc;
+    return launch_attend(ctx, q, K, V, out_idx, k, scale, out);
 }
 
 int spotlight_sparse_decode(spotlight_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* idx,

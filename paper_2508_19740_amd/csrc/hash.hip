@@ -235,14 +235,23 @@ __global__ __launch_bounds__(kThreads) void hash_kernel(HashArgs a)
 // or staging the weights through LDS with coalesced loads, measured slower: rows are 256 B or more
 // apart, so every 16-byte load of a wave touches 64 cache lines and issue time dominates.)  The only LDS traffic is the broadcast of the hidden
 // activations.  Same arithmetic, same order as the tiled kernel.
+// Two independent jobs in one launch (the decode step hashes the queries and the appended keys
+// together): workgroups [0, n_first) run job[0], the rest job[1].
+struct HashVecArgs {
+    HashArgs job[2];
+    int n_first;
+};
+
 template <typename XT, typename WT>
-__global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashArgs a)
+__global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashVecArgs jobs)
 {
     extern __shared__ __align__(16) float act[];  // hidden activations, or x itself for the linear hash
     constexpr int G16 = kHeadDim / 8;             // groups of 8 in a run of 128 weights
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int xhead = blockIdx.x;
+    const bool second = static_cast<int>(blockIdx.x) >= jobs.n_first;   // uniform over the workgroup
+    const HashArgs& a = jobs.job[second ? 1 : 0];
+    const int xhead = static_cast<int>(blockIdx.x) - (second ? jobs.n_first : 0);
     const int whead = (xhead % a.heads_per_batch) / a.group;
     const XT* x = static_cast<const XT*>(a.x) + xhead * a.x_head_stride + a.x_row0 * kHeadDim;
     const int act_dim = a.hidden > 0 ? a.hidden : kHeadDim;   // multiple of 128
@@ -335,11 +344,16 @@ __global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashArgs a)
 }
 
 template <typename XT, typename WT>
-int run_vec(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
+int run_vec(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, const HashArgs* b, int n_xheads_b, int stage)
 {
     const size_t lds = sizeof(float) * (a.hidden > 0 ? a.hidden : kHeadDim);
+    HashVecArgs jobs;
+    jobs.job[0] = a;
+    jobs.job[1] = b ? *b : a;
+    jobs.n_first = n_xheads;
+    const int grid = n_xheads + (b ? n_xheads_b : 0);
     StageTimer timer(ctx, stage);
-    hipLaunchKernelGGL((hash_vec_kernel<XT, WT>), dim3(static_cast<unsigned>(n_xheads)), dim3(kThreads), lds, ctx->stream, a);
+    hipLaunchKernelGGL((hash_vec_kernel<XT, WT>), dim3(static_cast<unsigned>(grid)), dim3(kThreads), lds, ctx->stream, jobs);
     return hip_rc(hipGetLastError());
 }
 
@@ -381,7 +395,7 @@ int run_tk(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
 {
     const size_t cap = static_cast<size_t>(ctx->max_lds);
     // a single vector per head, hidden width a multiple of 128: the latency-oriented kernel
-    if (a.n_rows == 1 && a.hidden % kHeadDim == 0) return run_vec<XT, WT>(ctx, a, n_xheads, stage);
+    if (a.n_rows == 1 && a.hidden % kHeadDim == 0) return run_vec<XT, WT>(ctx, a, n_xheads, nullptr, 0, stage);
     if (a.n_rows >= 32 && lds_bytes(32, a.hidden) <= cap) return run_ks<XT, WT, 32>(ctx, a, n_xheads, stage);
     if (a.n_rows >= 4 && lds_bytes(8, a.hidden) <= cap) return run_ks<XT, WT, 8>(ctx, a, n_xheads, stage);
     return run_ks<XT, WT, 1>(ctx, a, n_xheads, stage);
@@ -389,11 +403,8 @@ int run_tk(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
 
 }  // namespace
 
-int launch_hash(spotlight_ctx* ctx, const HashLaunch& h, int stage)
+static HashArgs make_args(const HashLaunch& h)
 {
-    if (h.n_rows <= 0 || h.n_xheads <= 0) return SPOTLIGHT_OK;
-    // the weight rows are read 8 elements at a time
-    if (h.hidden % 8 != 0) return SPOTLIGHT_ERR_UNSUPPORTED;
     HashArgs a;
     a.x = h.x;
     a.x_head_stride = h.x_head_stride;
@@ -413,11 +424,37 @@ int launch_hash(spotlight_ctx* ctx, const HashLaunch& h, int stage)
     a.code_row0 = h.code_row0;
     a.zero = h.zero;
     a.zero_words = h.zero_words;
+    return a;
+}
+
+int launch_hash(spotlight_ctx* ctx, const HashLaunch& h, int stage)
+{
+    if (h.n_rows <= 0 || h.n_xheads <= 0) return SPOTLIGHT_OK;
+    // the weight rows are read 8 elements at a time
+    if (h.hidden % 8 != 0) return SPOTLIGHT_ERR_UNSUPPORTED;
+    const HashArgs a = make_args(h);
     const bool xb = h.x_dtype == SPOTLIGHT_BF16, wb = h.w_dtype == SPOTLIGHT_BF16;
     if (xb && wb) return run_tk<bf16_raw, bf16_raw>(ctx, a, h.n_xheads, stage);
     if (xb && !wb) return run_tk<bf16_raw, float>(ctx, a, h.n_xheads, stage);
     if (!xb && wb) return run_tk<float, bf16_raw>(ctx, a, h.n_xheads, stage);
     return run_tk<float, float>(ctx, a, h.n_xheads, stage);
+}
+
+int launch_hash_pair(spotlight_ctx* ctx, const HashLaunch& h0, const HashLaunch& h1, int stage)
+{
+    const bool one_launch = h0.n_rows == 1 && h1.n_rows == 1 && h0.n_xheads > 0 && h1.n_xheads > 0 &&
+                            h0.hidden == h1.hidden && h0.hidden % kHeadDim == 0 && h0.L == h1.L &&
+                            h0.x_dtype == h1.x_dtype && h0.w_dtype == h1.w_dtype;
+    if (!one_launch) {
+        const int rc = launch_hash(ctx, h0, stage);
+        return rc != SPOTLIGHT_OK ? rc : launch_hash(ctx, h1, stage);
+    }
+    const HashArgs a = make_args(h0), b = make_args(h1);
+    const bool xb = h0.x_dtype == SPOTLIGHT_BF16, wb = h0.w_dtype == SPOTLIGHT_BF16;
+    if (xb && wb) return run_vec<bf16_raw, bf16_raw>(ctx, a, h0.n_xheads, &b, h1.n_xheads, stage);
+    if (xb && !wb) return run_vec<bf16_raw, float>(ctx, a, h0.n_xheads, &b, h1.n_xheads, stage);
+    if (!xb && wb) return run_vec<float, bf16_raw>(ctx, a, h0.n_xheads, &b, h1.n_xheads, stage);
+    return run_vec<float, float>(ctx, a, h0.n_xheads, &b, h1.n_xheads, stage);
 }
 
 }  // namespace spotlight

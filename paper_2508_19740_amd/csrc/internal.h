@@ -26,8 +26,8 @@ struct Plan {
     int max_splits;        // ceil(max_topk / kAttendMinRows)
     // workspace offsets in bytes
     size_t off_qcode;      // [B*Hq][W] query codes
-    size_t off_gcum;       // [B*Hq][L+1] cumulative distance histogram of the head
-    size_t off_blockcum;   // [B*Hq][max_blocks][L+1] cumulative histogram of each token block
+    size_t off_gcum;       // [B*Hq][L+2] cumulative histogram of the head (bin 0: forced tokens, bin d+1: distance d)
+    size_t off_blockcum;   // [B*Hq][max_blocks][L+2] cumulative histogram of each token block
     size_t off_blockmeta;  // [B*Hq][max_blocks] {candidate bound, four sub-list lengths}
     size_t off_cand;       // [B*Hq][max_blocks][4][kCandCap/4] candidates (distance << 16 | block offset)
     size_t off_part_ml;    // [B*Hq][max_splits] {max, sum} of each attention split
@@ -116,8 +116,11 @@ struct HashLaunch {
     int zero_words;
 };
 int launch_hash(spotlight_ctx* ctx, const HashLaunch& a, int stage);
+// Two hash jobs; one launch when both hash a single vector per head with the same network shape.
+int launch_hash_pair(spotlight_ctx* ctx, const HashLaunch& a, const HashLaunch& b, int stage);
 
-int launch_retrieve(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens, int k,
+// The first n_sink and the last n_local tokens are always selected (0, 0: none).
+int launch_retrieve(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens, int k, int n_sink, int n_local,
                     int32_t* out_idx, uint16_t* out_dist);
 
 int launch_attend(spotlight_ctx* ctx, const void* q, const void* K, const void* V,

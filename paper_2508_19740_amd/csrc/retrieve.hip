@@ -23,6 +23,14 @@
 //
 // The result is exactly the first k tokens in (distance, token index) order, listed by increasing
 // token index, with integer arithmetic only: identical bits on every run.
+//
+// Forced tokens (the first n_sink and the last n_local of the cache: the "Sink" and "Local"
+// columns of the paper's comparison with MagicPIG; a local window of one is the current token that
+// Eq. 1 concatenates) use the same machinery: every histogram has one bin below distance 0.  A
+// token is counted in bin 0 if it is forced and in bin distance + 1 otherwise, so forced tokens
+// sort in front of everything else and the selection is "forced tokens, then the nearest of the
+// others", k in all.  The shift costs nothing (the popcount accumulator starts at 1) and only the
+// few blocks that hold forced tokens take the path that looks at token positions.
 #include "internal.h"
 
 #include <type_traits>
@@ -88,6 +96,7 @@ struct ScoreArgs {
     BlockMeta* blockmeta;
     uint32_t* cand;
     int64_t n_tokens, Nmax;
+    int64_t n_sink, local_begin;   // token t is forced iff t < n_sink or t >= local_begin
     int Hkv, nblk, max_blocks, k, total_tasks, tasks_per_group;
 };
 
@@ -95,11 +104,16 @@ struct ScoreArgs {
 // tasks_per_group CONSECUTIVE tasks, which mostly belong to one head, and keeps that head's
 // cumulative histogram in LDS across them, so the (slow, device-wide) atomics into the head's
 // global histogram happen once per run of tasks instead of once per block.
+// Wavefronts per SIMD the register allocation must leave room for.  The allocator lands on either
+// side of the 128-register line for 256-bit codes with four heads per group depending on unrelated
+// code; four workgroups per compute unit measured 4 % faster than three there.
+constexpr int score_min_waves(int W, int G) { return (W == 8 && G == 4) ? 4 : 1; }
+
 template <int W, int G, int R>
-__global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
+__global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(ScoreArgs a)
 {
     constexpr int L = W * 32;
-    constexpr int BINS = L + 1;
+    constexpr int BINS = L + 2;            // bin 0: forced tokens; bin d + 1: distance d
     constexpr int CH = (BINS + 63) / 64;   // bins per lane in the scan
     // lanes per key: 16 bytes per lane when the code is 16, 32 or 64 bytes, else one lane per key
     constexpr int LPK = (W == 4 || W == 8 || W == 16) ? W / 4 : 1;
@@ -161,6 +175,38 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
 #pragma unroll
             for (int w = 0; w < CWL; ++w) qc[g][w] = a.qcode[(bh0 + g) * W + sub * CWL + w];
 
+        // Forced tokens of this block, as offsets into it: [0, sink_end) and [local_off, n_blk).
+        // Only the first and the last blocks of a head have any.  The main loop below counts them
+        // at the bin of their distance like every other token; here they are moved to bin 0 of the
+        // histogram (the subtraction comes first: the counters wrap and come back).  The candidate
+        // lists keep the distance; select knows the forced tokens by position.
+        const int sink_end = static_cast<int>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), a.n_sink - t_begin)));
+        const int local_off = static_cast<int>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), a.local_begin - t_begin)));
+        if (sink_end > 0 || local_off < n_blk) {
+            const char* blk_base = reinterpret_cast<const char*>(a.codes + (static_cast<int64_t>(bk) * a.Nmax + t_begin) * W);
+            for (int off = tid; off < n_blk; off += kThreads) {
+                if (off >= sink_end && off < local_off) continue;
+                constexpr int CHUNK = W % 4 == 0 ? 4 : 1;   // words per load
+                uint32_t d[G];
+#pragma unroll
+                for (int g = 0; g < G; ++g) d[g] = 0;
+#pragma unroll 1
+                for (int w0 = 0; w0 < W; w0 += CHUNK) {
+                    uint32_t key[CHUNK];
+                    load_key<CHUNK>(blk_base, static_cast<uint32_t>(off) * (W * 4) + w0 * 4, key);
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+#pragma unroll
+                        for (int w = 0; w < CHUNK; ++w) d[g] += popc(key[w] ^ a.qcode[(bh0 + g) * W + w0 + w]);
+                }
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    atomicSub(&hist[(g * BINS + 1 + d[g]) * R + rep], 1u);
+                    atomicAdd(&hist[(g * BINS + 0) * R + rep], 1u);
+                }
+            }
+        }
+
         // distances of the 16 keys this lane owns, two per register
         uint32_t dv[G][kKPT / 2];
 #pragma unroll
@@ -184,7 +230,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
             for (int u = 0; u < KB; ++u) {
                 const int sl = bt * KB + u;
                 const bool valid = decltype(full)::value || sl * KPS + kq < n_blk;
-                uint32_t d[G];
+                uint32_t d[G];   // distances; the histogram bin is d + 1
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     d[g] = 0;
@@ -196,7 +242,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
                     const int j = sl / LPK;   // index among the keys this lane owns
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
-                        atomicAdd(&hist[(g * BINS + d[g]) * R + rep], 1u);
+                        atomicAdd(&hist[(g * BINS + 1 + d[g]) * R + rep], 1u);
                         if constexpr (decltype(full)::value) {   // both halves get written: no mask needed
                             dv[g][j >> 1] = (j & 1) ? (d[g] << 16) | dv[g][j >> 1] : d[g];
                         } else {
@@ -210,6 +256,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
         };
         if (n_blk == kTPB) score_block(std::true_type{});
         else score_block(std::false_type{});
+
         __syncthreads();
 
         // fold the replicas (rotated so that neighbouring threads hit different banks)
@@ -274,11 +321,12 @@ __global__ __launch_bounds__(kThreads) void score_kernel(ScoreArgs a)
 #pragma unroll
             for (int i = 0; i < kKPT; ++i) {
                 const uint32_t d = (dv[g][i >> 1] >> ((i & 1) * 16)) & 0xffffu;
-                const bool p = d <= thi;
+                const bool p = d < thi;   // bin d + 1 <= bound (thi is a bin; absent keys hold 0xffff)
                 const unsigned long long m = __ballot(p);
                 if (p) {
                     const uint32_t at = run + __builtin_popcountll(m & ((1ull << lane) - 1ull));
-                    if (at < static_cast<uint32_t>(kWaveCap)) cl[at] = (d << 16) | static_cast<uint32_t>((i * LPK + sub) * KPS + kq);
+                    if (at < static_cast<uint32_t>(kWaveCap))
+                        cl[at] = (d << 16) + (0x10000u | static_cast<uint32_t>((i * LPK + sub) * KPS + kq));   // entry: bin << 16 | offset
                 }
                 run += __builtin_popcountll(m);
             }
@@ -299,9 +347,10 @@ template <int W>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const uint32_t* __restrict__ codes, const uint32_t* __restrict__ qcode, const uint32_t* __restrict__ gcum,
     const uint32_t* __restrict__ blockcum, const BlockMeta* __restrict__ blockmeta, const uint32_t* __restrict__ cand,
-    int32_t* __restrict__ out_idx, int64_t n_tokens, int64_t Nmax, int Hq, int Hkv, int max_blocks, int k)
+    int32_t* __restrict__ out_idx, int64_t n_tokens, int64_t Nmax, int Hq, int Hkv, int max_blocks, int k,
+    int64_t n_sink, int64_t local_begin)
 {
-    constexpr int BINS = W * 32 + 1;
+    constexpr int BINS = W * 32 + 2;   // bin 0: forced tokens; bin d + 1: distance d
     constexpr int NW = kSelThreads / 64;
     constexpr int SUB = kThreads / 64;               // candidate sub-lists per block
     constexpr int PER = kWaveCap / kSelThreads;      // sub-list entries per thread (2)
@@ -375,6 +424,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 
     const int64_t t_begin = static_cast<int64_t>(blk) * kTPB;
     const int n_blk = static_cast<int>(min(static_cast<int64_t>(kTPB), n_tokens - t_begin));
+    // forced tokens of this block, as offsets into it: [0, sink_end) and [local_off, n_blk)
+    const uint32_t sink_end = static_cast<uint32_t>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), n_sink - t_begin)));
+    const uint32_t local_off = static_cast<uint32_t>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), local_begin - t_begin)));
     bool listed = T <= meta.bound;
 #pragma unroll
     for (int s = 0; s < SUB; ++s) listed = listed && meta.count[s] != kWaveFull;
@@ -384,7 +436,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
             for (int h = 0; h < PER; ++h) {
                 if (h * kSelThreads + tid < static_cast<int>(meta.count[s])) {
-                    const uint32_t d = ce[s][h] >> 16, off = ce[s][h] & (kTPB - 1);
+                    const uint32_t off = ce[s][h] & (kTPB - 1);
+                    const uint32_t d = (off < sink_end || off >= local_off) ? 0u : ce[s][h] >> 16;   // forced: bin 0
                     if (d < T) atomicOr(&lt_bits[off >> 5], 1u << (off & 31));
                     else if (d == T) atomicOr(&eq_bits[off >> 5], 1u << (off & 31));
                 }
@@ -400,12 +453,22 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         for (int off = tid; off < n_blk; off += kSelThreads) {
             uint32_t kw[W];
             load_key<W>(cbase, static_cast<uint32_t>(off) * (W * 4), kw);
-            uint32_t d = 0;
+            uint32_t d = 1;
 #pragma unroll
             for (int w = 0; w < W; ++w) d += popc(kw[w] ^ qc[w]);
+            if (static_cast<uint32_t>(off) < sink_end || static_cast<uint32_t>(off) >= local_off) d = 0;
             if (d < T) atomicOr(&lt_bits[off >> 5], 1u << (off & 31));
             else if (d == T) atomicOr(&eq_bits[off >> 5], 1u << (off & 31));
         }
+    }
+    // forced tokens are in bin 0 whether or not a list names them: marked by position
+    if (sink_end > 0 || local_off < static_cast<uint32_t>(n_blk)) {
+        uint32_t m = 0;
+        for (int bit = 0; bit < 32; ++bit) {
+            const uint32_t off = static_cast<uint32_t>(tid) * 32 + bit;
+            if (off < static_cast<uint32_t>(n_blk) && (off < sink_end || off >= local_off)) m |= 1u << bit;
+        }
+        if (m) atomicOr(T > 0 ? &lt_bits[tid] : &eq_bits[tid], m);
     }
     __syncthreads();
 
@@ -461,6 +524,7 @@ __global__ __launch_bounds__(kThreads) void dist_kernel(const uint32_t* __restri
 struct RetrieveArgs {
     const uint32_t* codes;
     int64_t n_tokens;
+    int64_t n_sink, local_begin;
     int k, nblk;
     int32_t* out_idx;
     uint16_t* out_dist;
@@ -470,7 +534,7 @@ template <int W, int G>
 int launch_score_wg(spotlight_ctx* ctx, const RetrieveArgs& a)
 {
     const Plan& p = ctx->plan;
-    constexpr int BINS = W * 32 + 1;
+    constexpr int BINS = W * 32 + 2;
     // histogram replicas: 8 if they fit in 32 KB of LDS (more did not make the LDS atomics faster
     // and make the per-block fold and re-zero slower), fewer for wide codes and big groups
     constexpr int kCap = 32768;
@@ -493,6 +557,8 @@ int launch_score_wg(spotlight_ctx* ctx, const RetrieveArgs& a)
     s.blockmeta = reinterpret_cast<BlockMeta*>(ctx->workspace + p.off_blockmeta);
     s.cand = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_cand);
     s.n_tokens = a.n_tokens;
+    s.n_sink = a.n_sink;
+    s.local_begin = a.local_begin;
     s.Nmax = p.Nmax;
     s.Hkv = p.Hkv;
     s.nblk = a.nblk;
@@ -532,7 +598,7 @@ int launch_w(spotlight_ctx* ctx, const RetrieveArgs& a)
                            reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_blockcum),
                            reinterpret_cast<const BlockMeta*>(ctx->workspace + p.off_blockmeta),
                            reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_cand), a.out_idx, a.n_tokens,
-                           p.Nmax, p.Hq, p.Hkv, p.max_blocks, a.k);
+                           p.Nmax, p.Hq, p.Hkv, p.max_blocks, a.k, a.n_sink, a.local_begin);
         if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
     }
     if (a.out_dist) {
@@ -546,12 +612,14 @@ int launch_w(spotlight_ctx* ctx, const RetrieveArgs& a)
 
 }  // namespace
 
-int launch_retrieve(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens, int k, int32_t* out_idx,
-                    uint16_t* out_dist)
+int launch_retrieve(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens, int k, int n_sink, int n_local,
+                    int32_t* out_idx, uint16_t* out_dist)
 {
     RetrieveArgs a;
     a.codes = codes;
     a.n_tokens = n_tokens;
+    a.n_sink = n_sink;
+    a.local_begin = n_tokens - n_local;
     a.k = k;
     a.nblk = static_cast<int>((n_tokens + kTPB - 1) / kTPB);
     a.out_idx = out_idx;

@@ -1,0 +1,137 @@
+"""GPU parity of the one-call decode step (appended-key hash + query hash in one launch, retrieval
+with forced sink / local tokens, attention) against the oracle's decode step."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workload as wl
+from gpu_common import Case
+
+pytestmark = pytest.mark.gpu
+ATTN_TOL = 2e-3
+
+C = wl.CONFIGS
+SMALL = {
+    "c1": C["C1"],
+    "c2_ragged": C["C2"].scaled(n_q_heads=4, n_kv_heads=4, n_tokens=9000 + 37, topk=181, needles=5),
+    "c4_gqa": C["C4"].scaled(batch=2, n_tokens=5000 + 13, topk=300, needles=3),
+    "c5_512": C["C5-512"].scaled(batch=1, n_q_heads=2, n_kv_heads=2, n_tokens=3000 + 5, topk=100, needles=2, extra_tokens=3),
+    "lin_128": C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=2049, topk=90, hidden=0, needles=2),
+    "odd_words": C["C2"].scaled(n_q_heads=2, n_kv_heads=1, n_tokens=1500, topk=133, code_bits=96, hidden=64, needles=2),
+    "block_edge": C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=3 * 4096, topk=200, needles=2),
+    "g8": C["C4"].scaled(batch=1, n_q_heads=8, n_kv_heads=1, n_tokens=4200, topk=100, code_bits=128, hidden=256, needles=1),
+}
+FORCED = [(0, 0), (4, 64), (0, 1), (7, 0)]
+
+
+@pytest.fixture(scope="module", params=sorted(SMALL))
+def case(request):
+    c = Case(SMALL[request.param])
+    cfg = c.cfg
+    # code cache of all tokens but the last, by the oracle (no oracle input comes from the GPU)
+    c.base_codes = c.oracle_codes(0, cfg.n_tokens - 1)
+    yield c
+    c.close()
+
+
+@pytest.mark.parametrize("forced", FORCED)
+def test_decode_step_matches_oracle(case, forced):
+    cfg = case.cfg
+    n_sink, n_local = forced
+    n = cfg.n_tokens
+    want_codes = case.base_codes.clone()
+    want_idx, want_out = oracle.decode_step(case.w.q, case.hK, case.hV, *case.hweights, want_codes, n, cfg.topk,
+                                            n_sink, n_local, case.scale)
+    case.codes.copy_(case.base_codes)
+    idx, out = case.ctx.decode_step(case.q, case.K, case.V, *case.weights, case.codes, n, cfg.topk, n_sink, n_local)
+    assert torch.equal(case.codes.cpu(), want_codes)                 # the appended key's code, nothing else
+    assert torch.equal(idx.cpu(), want_idx)
+    assert float((out.cpu() - want_out).abs().max()) <= ATTN_TOL
+    if n_sink or n_local:
+        got = idx.cpu()
+        for t in list(range(n_sink)) + list(range(n - n_local, n)):
+            assert (got == t).any(dim=-1).all()
+
+
+def test_forced_tokens_across_block_borders(case):
+    """Sink and local windows longer than a 4096-token block, and windows that meet."""
+    cfg = case.cfg
+    n = cfg.n_tokens
+    for n_sink, n_local, k in ((min(n // 3, 4100), min(n // 3, 4200), min(n, 2 * (n // 3) + 40)),
+                               (n // 2, n - n // 2, n), (n, n, n)):
+        want_codes = case.base_codes.clone()
+        want_idx, _ = oracle.decode_step(case.w.q, case.hK, case.hV, *case.hweights, want_codes, n, k,
+                                         n_sink, n_local, case.scale)
+        case.codes.copy_(case.base_codes)
+        idx, _ = case.ctx.decode_step(case.q, case.K, case.V, *case.weights, case.codes, n, k, n_sink, n_local)
+        assert torch.equal(idx.cpu(), want_idx), (n_sink, n_local, k)
+
+
+def test_step_without_forced_tokens_equals_the_three_calls(case):
+    cfg = case.cfg
+    n = cfg.n_tokens
+    case.codes.copy_(case.base_codes)
+    idx, out = case.ctx.decode_step(case.q, case.K, case.V, *case.weights, case.codes, n, cfg.topk)
+    c2 = case.base_codes.to(case.dev)
+    case.ctx.hash_keys(case.K, *case.weights, n - 1, 1, c2)
+    idx2 = case.ctx.retrieve_topk(case.q, *case.weights, c2, n, cfg.topk)
+    out2 = case.ctx.sparse_decode(case.q, case.K, case.V, idx2)
+    assert torch.equal(case.codes, c2)
+    assert torch.equal(idx, idx2)
+    assert torch.equal(out, out2)
+
+
+def test_decode_step_rejects_bad_arguments(case):
+    import paper_2508_19740_amd as sp
+    cfg = case.cfg
+    n = cfg.n_tokens
+    args = (case.q, case.K, case.V, *case.weights, case.codes)
+    for kw in (dict(n_tokens=n, k=10, n_sink=8, n_local=3),       # 11 forced tokens, k = 10
+               dict(n_tokens=n, k=10, n_sink=-1, n_local=0),
+               dict(n_tokens=n, k=10, n_sink=0, n_local=-2),
+               dict(n_tokens=0, k=1, n_sink=0, n_local=0),
+               dict(n_tokens=cfg.max_tokens + 1, k=1, n_sink=0, n_local=0),
+               dict(n_tokens=n, k=n + 1, n_sink=0, n_local=0)):
+        with pytest.raises(sp.SpotlightError) as e:
+            case.ctx.decode_step(*args, kw["n_tokens"], kw["k"], kw["n_sink"], kw["n_local"])
+        assert e.value.rc == sp.ERR_INVALID_ARG
+
+
+def test_decode_step_in_a_hip_graph():
+    """The call is five kernel launches and nothing else, so it can be captured.  Replayed several
+    times with eager work and synchronisations in between; every replay equals the eager result."""
+    cfg = C["C2"].scaled(n_q_heads=4, n_kv_heads=4, n_tokens=9000 + 37, topk=181, needles=5)
+    c = Case(cfg)
+    try:
+        n = cfg.n_tokens
+        base = c.oracle_codes(0, n - 1).to(c.dev)
+        c.codes.copy_(base)
+        idx_e, out_e = c.ctx.decode_step(c.q, c.K, c.V, *c.weights, c.codes, n, cfg.topk, 4, 64)
+        codes_e = c.codes.clone()
+        torch.cuda.synchronize()
+        idx_g = torch.empty_like(idx_e)
+        out_g = torch.empty_like(out_e)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        c.codes.copy_(base)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph.capture_begin()
+            c.ctx.decode_step(c.q, c.K, c.V, *c.weights, c.codes, n, cfg.topk, 4, 64, out_idx=idx_g, out=out_g)
+            graph.capture_end()
+        torch.cuda.synchronize()
+        for rep in range(4):
+            c.codes.copy_(base)
+            idx_g.fill_(-7)
+            out_g.fill_(float("nan"))
+            junk = (torch.randn(1 << 20, device=c.dev) * (rep + 1)).sum()     # eager work between replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.isfinite(junk)
+            assert torch.equal(c.codes, codes_e), rep
+            assert torch.equal(idx_g, idx_e), rep
+            assert torch.equal(out_g, out_e), rep
+    finally:
+        c.close()
