@@ -90,6 +90,24 @@ def uniform_int(seed: int, tag: int, start: int, count: int, modulus: int,
     return random_bits32(seed, tag, start, count, device) % modulus
 
 
+def rotation_matrix(seed: int, tag: int, start: int, d: int) -> torch.Tensor:
+    """A d x d rotation (orthogonal, determinant +1) as the paper's appendix on LSH weight
+    initialisation builds it: QR decomposition of a matrix of independent N(0,1) entries (here by
+    modified Gram-Schmidt in float64 on the host, so that the result does not depend on a linear
+    algebra library), the first column negated if the determinant is negative.  float32, rows are
+    the hyperplane normals."""
+    a = normal(seed, tag, start, d * d).double().view(d, d)
+    q = torch.zeros(d, d, dtype=torch.float64)
+    for j in range(d):
+        v = a[:, j].clone()
+        for _ in range(2):                       # second pass: re-orthogonalisation
+            v = v - q[:, :j] @ (q[:, :j].T @ v)
+        q[:, j] = v / v.norm()
+    if torch.linalg.det(q) < 0:
+        q[:, 0] = -q[:, 0]
+    return q.float()
+
+
 _TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 
@@ -110,6 +128,7 @@ class Config:
     seed: int
     head_dim: int = 128
     extra_tokens: int = 0    # room for appended keys (cache growth)
+    lsh_init: str = "gaussian"   # linear hash (hidden == 0) only: "gaussian" | "rotation"
 
     @property
     def max_tokens(self) -> int:
@@ -182,6 +201,14 @@ class Workload:
         """W1 [Hkv, h, d], b1 [Hkv, h], W2 [Hkv, L, h]; with hidden == 0, W1 is R [Hkv, L, d]."""
         c = self.cfg
         d, h, L = c.head_dim, c.hidden, c.code_bits
+        if h == 0 and c.lsh_init == "rotation":
+            # Angular LSH initialised with rotation matrices (appendix "LSH Weight Initialization"):
+            # a code longer than d bits takes L / d independent rotations side by side.
+            assert L % d == 0, "rotation init needs code_bits to be a multiple of head_dim"
+            blocks = [rotation_matrix(c.seed, TAG_W1, (hk * (L // d) + j) * d * d, d)
+                      for hk in range(c.n_kv_heads) for j in range(L // d)]
+            w1 = torch.stack(blocks).view(c.n_kv_heads, L, d)
+            return (w1.to(self.w_t).contiguous().to(device), None, None)
         if h == 0:
             w1 = 0.05 * normal(c.seed, TAG_W1, 0, c.n_kv_heads * L * d, device)
             return (w1.view(c.n_kv_heads, L, d).to(self.w_t).contiguous(), None, None)
