@@ -52,6 +52,7 @@ int make_plan(const spotlight_config* c, Plan* p)
     p->off_cand = off;      off = align_up(off + BH * p->max_blocks * static_cast<size_t>(kCandCap) * 4, 256);
     p->off_part_ml = off;   off = align_up(off + BH * p->max_splits * 8, 256);
     p->off_part_acc = off;  off = align_up(off + BH * p->max_splits * static_cast<size_t>(kHeadDim) * 4, 256);
+    p->off_wnorm = off;     off = align_up(off + static_cast<size_t>(p->Hkv) * p->L * 4, 256);
     p->total_bytes = off;
     return SPOTLIGHT_OK;
 }
@@ -200,6 +201,7 @@ static HashLaunch key_job(const spotlight_ctx* ctx, const void* K, const spotlig
     h.code_row0 = t0;
     h.zero = nullptr;
     h.zero_words = 0;
+    h.wnorm = reinterpret_cast<float*>(ctx->workspace + p.off_wnorm);
     return h;
 }
 
@@ -228,6 +230,7 @@ static HashLaunch query_job(const spotlight_ctx* ctx, const void* q, const spotl
     h.code_row0 = 0;
     h.zero = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_gcum);
     h.zero_words = p.L + 2;
+    h.wnorm = nullptr;
     return h;
 }
 

@@ -14,6 +14,8 @@
 //          ballot of (y > 0) IS the pair of packed words.  No boolean tensor is ever stored.
 #include "internal.h"
 
+#include <stdlib.h>
+
 namespace spotlight {
 namespace {
 
@@ -115,7 +117,10 @@ struct HashArgs {
     int64_t code_head_stride, code_row0;
     uint32_t* zero;
     int zero_words;
+    float* wnorm;   // scratch for the output-row norms of the matrix-core path, or null
 };
+
+__device__ __forceinline__ int whead_of(const HashArgs& a, int xhead) { return (xhead % a.heads_per_batch) / a.group; }
 
 // acc[t] += sum over n8*8 consecutive weights of `row` times act[(i)*stride + t], in increasing i,
 // one fused multiply-add per term.  PF groups of 8 weights are fetched ahead of their use.
@@ -225,6 +230,245 @@ __global__ __launch_bounds__(kThreads) void hash_kernel(HashArgs a)
                 if (2 * pair + 1 < a.W) cbase[static_cast<int64_t>(r) * a.W + 2 * pair + 1] = static_cast<uint32_t>(m >> 32);
             }
         }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Bulk hashing with the second layer on the matrix cores.
+//
+// Phase 1 is the canonical binary32 chain above (the hidden activations feed a non-linear function,
+// so nothing but the defined arithmetic will do).  Phase 2, Y = H W2^T for a tile of 32 vectors, is
+// a dense contraction and runs as v_mfma_f32_32x32x16_bf16: W2 is bfloat16 as stored, and each
+// activation h is split on the fly into hi + lo (both bfloat16, |h - hi - lo| <= 2^-15 |h|), so
+// the products are exact and two accumulating MFMA passes give y to within
+//     |y_mfma - y_canonical| <= eps * sum_i |W2[j][i] h_i| <= eps * ||W2[j]|| * ||h||
+// with eps = 1.01 * (hidden * (2^-24 + 1.01 * 2^-22) + 2^-15):  hidden roundings of 2^-24 in the
+// canonical chain, at most 2 * hidden additions in the matrix core each assumed to err by at most
+// one unit in the last place of binary32 whatever their order, and the split residue.
+// The sign of y_mfma is therefore the canonical sign wherever |y_mfma| exceeds that bound; the few
+// outputs that do not (about 0.2 %) are recomputed with the canonical chain from the binary32
+// activations still in LDS.  The codes are identical to the all-binary32 kernel's, bit for bit.
+//
+// The 32 columns of an MFMA tile are the 32 outputs of ONE code word in bit order (column c is
+// output (31 - c) * W + word), so a wave ballot over an accumulator register is two packed words.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kMfmaTile = 32;       // vectors per tile (rows of the MFMA)
+constexpr int kMfmaListCap = 1024;  // outputs of a tile that may go to the canonical recomputation
+
+struct MfmaLds {   // lives in the x tile's LDS once phase 1 is done with it
+    float part[8][kMfmaTile];
+    float hn[kMfmaTile];              // ||h_t||
+    uint32_t codes[kMfmaTile][16];
+    uint16_t list[kMfmaListCap];
+    uint32_t count;
+};
+static_assert(sizeof(MfmaLds) <= sizeof(float) * kHeadDim * kMfmaTile, "fits in the x tile");
+
+// hi / lo split of 8 activations into two MFMA operands
+__device__ __forceinline__ void split8(const float (&h)[8], bf16x8_t& hi, bf16x8_t& lo)
+{
+    union { bf16x8_t v; uint32_t u[4]; } a, b;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t x0 = __float_as_uint(h[2 * p]), x1 = __float_as_uint(h[2 * p + 1]);
+        const uint32_t h0 = x0 & 0xffff0000u, h1 = x1 & 0xffff0000u;                 // truncated high parts
+        const float r0 = h[2 * p] - __uint_as_float(h0), r1 = h[2 * p + 1] - __uint_as_float(h1);   // exact
+        const uint32_t l0 = (__float_as_uint(r0) + 0x8000u) & 0xffff0000u;          // rounded low parts
+        const uint32_t l1 = (__float_as_uint(r1) + 0x8000u) & 0xffff0000u;
+        a.u[p] = (h0 >> 16) | h1;
+        b.u[p] = (l0 >> 16) | l1;
+    }
+    hi = a.v;
+    lo = b.v;
+}
+
+// ||W2[j]|| of every output row of every weight head, for the bound above.
+__global__ __launch_bounds__(kThreads) void w2_norm_kernel(const bf16_raw* __restrict__ w2, float* __restrict__ wnorm,
+                                                          int n_rows, int hidden)
+{
+    const int j = blockIdx.x * kThreads + threadIdx.x;
+    if (j >= n_rows) return;
+    float s = 0.0f;
+    for (int g = 0; g < hidden / 8; ++g) {
+        float wv[8];
+        load8(w2 + static_cast<int64_t>(j) * hidden + g * 8, wv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s = __builtin_fmaf(wv[e], wv[e], s);
+    }
+    wnorm[j] = __builtin_sqrtf(s);
+}
+
+// NBW: code words (MFMA column blocks) per wavefront = ceil(W / 4).
+template <typename XT, int NBW>
+__global__ __launch_bounds__(kThreads) void hash_mfma_kernel(HashArgs a, const float* __restrict__ wnorm, float eps,
+                                                            int tiles_per_group)
+{
+    using WT = bf16_raw;
+    constexpr int TK = kMfmaTile;
+    extern __shared__ __align__(16) float lds[];
+    float* xs = lds;                                   // [128][TK], later MfmaLds
+    float* hs = lds + kHeadDim * TK;                   // [hidden][TK]
+    MfmaLds& m = *reinterpret_cast<MfmaLds*>(xs);
+    float* hn = m.hn;
+    const float* wn = wnorm + static_cast<int64_t>(whead_of(a, blockIdx.y)) * a.L;   // ||W2[j]|| of this head
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int xhead = blockIdx.y;
+    const int whead = (xhead % a.heads_per_batch) / a.group;
+    const WT* w1 = static_cast<const WT*>(a.w1) + static_cast<int64_t>(whead) * a.hidden * kHeadDim;
+    const WT* b1 = static_cast<const WT*>(a.b1) + static_cast<int64_t>(whead) * a.hidden;
+    const WT* w2 = static_cast<const WT*>(a.w2) + static_cast<int64_t>(whead) * a.L * a.hidden;
+    const int n8 = a.hidden / 8;
+
+    const int64_t n_tiles = (a.n_rows + TK - 1) / TK;
+    const int64_t tile0 = static_cast<int64_t>(blockIdx.x) * tiles_per_group;
+    const int64_t tile1 = min(n_tiles, tile0 + tiles_per_group);
+    for (int64_t tile = tile0; tile < tile1; ++tile) {
+        const int64_t r0 = tile * TK;
+        const int rows = static_cast<int>(min(static_cast<int64_t>(TK), a.n_rows - r0));
+        __syncthreads();   // the previous tile is done with LDS
+
+        // ---- stage the x tile, transposed to [k][t], rows past the end as zeros
+        const XT* xbase = static_cast<const XT*>(a.x) + xhead * a.x_head_stride + (a.x_row0 + r0) * kHeadDim;
+        for (int e = tid; e < TK * (kHeadDim / 8); e += kThreads) {
+            const int t = e / (kHeadDim / 8), k8 = e % (kHeadDim / 8);
+            float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if (t < rows) load8(xbase + static_cast<int64_t>(t) * kHeadDim + k8 * 8, v);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) xs[(k8 * 8 + j) * TK + t] = v[j];
+        }
+        __syncthreads();
+
+        // ---- phase 1 (canonical): hidden activations
+        for (int i = tid; i < a.hidden; i += kThreads) {
+            float acc[TK];
+            const float bias = load1(b1 + i);
+#pragma unroll
+            for (int t = 0; t < TK; ++t) acc[t] = bias;
+            dot_rows<WT, TK, 1>(w1 + static_cast<int64_t>(i) * kHeadDim, kHeadDim / 8, xs, TK, acc);
+#pragma unroll
+            for (int t = 0; t < TK; ++t) hs[i * TK + t] = silu(acc[t]);
+        }
+        __syncthreads();
+
+        // ---- norms of the activation rows; the x tile's LDS becomes scratch
+        {
+            const int t = tid & (TK - 1), part = tid / TK;   // 8 partial sums per vector
+            float s = 0.0f;
+            for (int i = part; i < a.hidden; i += kThreads / TK) s = __builtin_fmaf(hs[i * TK + t], hs[i * TK + t], s);
+            m.part[part][t] = s;
+            if (tid == 0) m.count = 0;
+        }
+        __syncthreads();
+        if (tid < TK) {
+            float s = 0.0f;
+#pragma unroll
+            for (int p8 = 0; p8 < 8; ++p8) s += m.part[p8][tid];
+            hn[tid] = __builtin_sqrtf(s);
+        }
+        __syncthreads();
+
+        // ---- phase 2 on the matrix cores: wave w owns code words w, w + 4, ...
+        const int c = lane & 31, half = lane >> 5;
+        f32x16_t acc[NBW];
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+        const WT* brow[NBW];
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb) {
+            const int word = wave + 4 * nb;
+            const int j = word < a.W ? (31 - c) * a.W + word : 0;
+            brow[nb] = w2 + static_cast<int64_t>(j) * a.hidden + 8 * half;
+        }
+        const int n_ks = a.hidden / 16;
+        union BFrag { bf16x8_t v; uint4 u; };
+        BFrag bnext[NBW];
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb) bnext[nb].u = *reinterpret_cast<const uint4*>(brow[nb]);
+        for (int ks = 0; ks < n_ks; ++ks) {
+            BFrag b[NBW];
+#pragma unroll
+            for (int nb = 0; nb < NBW; ++nb) b[nb] = bnext[nb];
+            if (ks + 1 < n_ks) {   // the next step's weights are requested before this step's arithmetic
+#pragma unroll
+                for (int nb = 0; nb < NBW; ++nb) bnext[nb].u = *reinterpret_cast<const uint4*>(brow[nb] + (ks + 1) * 16);
+            }
+            float h8[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h8[e] = hs[(ks * 16 + 8 * half + e) * TK + c];
+            bf16x8_t ahi, alo;
+            split8(h8, ahi, alo);
+#pragma unroll
+            for (int nb = 0; nb < NBW; ++nb) {
+                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ahi, b[nb].v, acc[nb], 0, 0, 0);
+                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(alo, b[nb].v, acc[nb], 0, 0, 0);
+            }
+        }
+
+        // ---- signs, ballot-pack, and the list of outputs too close to zero to trust
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb) {
+            const int word = wave + 4 * nb;
+            if (word >= a.W) continue;   // uniform over the wavefront
+            const float tcol = eps * wn[(31 - c) * a.W + word];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int t = (v / 4) * 8 + half * 4 + (v % 4);
+                const float y = acc[nb][v];
+                const float thr = __builtin_fmaf(tcol, hn[t], 1e-30f);
+                const bool sure = __builtin_fabsf(y) > thr;   // false for NaN
+                const unsigned long long pos = __ballot(y > 0.0f);
+                if (c == 0) m.codes[t][word] = half ? static_cast<uint32_t>(pos >> 32) : static_cast<uint32_t>(pos);
+                if (!sure) {
+                    const uint32_t at = atomicAdd(&m.count, 1u);
+                    if (at < static_cast<uint32_t>(kMfmaListCap))
+                        m.list[at] = static_cast<uint16_t>(t | (word << 5) | (c << 9));
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- canonical recomputation of the listed outputs (of every output if the list overflowed)
+        const uint32_t listed = m.count;
+        if (listed <= static_cast<uint32_t>(kMfmaListCap)) {
+            for (uint32_t e = tid; e < listed; e += kThreads) {
+                const int t = m.list[e] & 31, word = (m.list[e] >> 5) & 15, col = m.list[e] >> 9;
+                const WT* row = w2 + static_cast<int64_t>((31 - col) * a.W + word) * a.hidden;
+                float y = 0.0f;
+                for (int g = 0; g < n8; ++g) {
+                    float wv[8];
+                    load8(row + g * 8, wv);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) y = __builtin_fmaf(wv[q], hs[(g * 8 + q) * TK + t], y);
+                }
+                const uint32_t bit = 1u << col;
+                if (((m.codes[t][word] & bit) != 0) != (y > 0.0f)) atomicXor(&m.codes[t][word], bit);
+            }
+        } else {
+            for (int item = tid; item < TK * a.L; item += kThreads) {
+                const int t = item % TK, j = item / TK;
+                const WT* row = w2 + static_cast<int64_t>(j) * a.hidden;
+                float y = 0.0f;
+                for (int g = 0; g < n8; ++g) {
+                    float wv[8];
+                    load8(row + g * 8, wv);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) y = __builtin_fmaf(wv[q], hs[(g * 8 + q) * TK + t], y);
+                }
+                const int word = j % a.W, col = 31 - j / a.W;
+                const uint32_t bit = 1u << col;
+                if (((m.codes[t][word] & bit) != 0) != (y > 0.0f)) atomicXor(&m.codes[t][word], bit);
+            }
+        }
+        __syncthreads();
+
+        // ---- the tile's codes: rows * W consecutive words
+        uint32_t* cbase = a.codes + xhead * a.code_head_stride + (a.code_row0 + r0) * a.W;
+        for (int e = tid; e < rows * a.W; e += kThreads) cbase[e] = m.codes[e / a.W][e % a.W];
     }
 }
 
@@ -390,10 +634,52 @@ int run_ks(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
     return run<XT, WT, TK, 1>(ctx, a, n_xheads, stage);
 }
 
+// Second layer on the matrix cores: bfloat16 weights, hidden a multiple of 16, at least one full tile.
+template <typename XT, int NBW>
+int run_mfma_nbw(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage, size_t lds, float* wnorm)
+{
+    auto kern = hash_mfma_kernel<XT, NBW>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return SPOTLIGHT_ERR_HIP;
+    }
+    const int64_t tiles = (a.n_rows + kMfmaTile - 1) / kMfmaTile;
+    // a workgroup takes a run of tiles of one head (the output-row norms are computed once per run),
+    // short enough that the grid still has a few thousand workgroups
+    int tpg = 8;
+    while (tpg > 1 && ((tiles + tpg - 1) / tpg) * n_xheads < 4096) tpg /= 2;
+    // error bound per unit of ||W2[j]|| * ||h||, see the kernel's header
+    const double eps = 1.01 * (a.hidden * (0x1p-24 + 1.01 * 0x1p-22) + 0x1p-15);
+    dim3 grid(static_cast<unsigned>((tiles + tpg - 1) / tpg), static_cast<unsigned>(n_xheads));
+    StageTimer timer(ctx, stage);
+    const int n_out = a.n_wheads * a.L;
+    hipLaunchKernelGGL(w2_norm_kernel, dim3(static_cast<unsigned>((n_out + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                       ctx->stream, static_cast<const bf16_raw*>(a.w2), wnorm, n_out, a.hidden);
+    hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, ctx->stream, a, wnorm, static_cast<float>(eps), tpg);
+    return hip_rc(hipGetLastError());
+}
+
+inline size_t mfma_lds_bytes(int hidden) { return sizeof(float) * kMfmaTile * (kHeadDim + hidden); }
+
+template <typename XT>
+int run_mfma(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage, float* wnorm)
+{
+    const size_t lds = mfma_lds_bytes(a.hidden);
+    if (a.W <= 4) return run_mfma_nbw<XT, 1>(ctx, a, n_xheads, stage, lds, wnorm);
+    if (a.W <= 8) return run_mfma_nbw<XT, 2>(ctx, a, n_xheads, stage, lds, wnorm);
+    return run_mfma_nbw<XT, 4>(ctx, a, n_xheads, stage, lds, wnorm);
+}
+
 template <typename XT, typename WT>
 int run_tk(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
 {
     const size_t cap = static_cast<size_t>(ctx->max_lds);
+    if constexpr (sizeof(WT) == 2) {
+        if (a.n_rows >= kMfmaTile && a.hidden > 0 && a.hidden % 16 == 0 && a.W <= 16 &&
+            mfma_lds_bytes(a.hidden) <= cap && a.wnorm && !getenv("SPOTLIGHT_NO_MFMA"))
+            return run_mfma<XT>(ctx, a, n_xheads, stage, a.wnorm);
+    }
     // a single vector per head, hidden width a multiple of 128: the latency-oriented kernel
     if (a.n_rows == 1 && a.hidden % kHeadDim == 0) return run_vec<XT, WT>(ctx, a, n_xheads, nullptr, 0, stage);
     if (a.n_rows >= 32 && lds_bytes(32, a.hidden) <= cap) return run_ks<XT, WT, 32>(ctx, a, n_xheads, stage);
@@ -424,6 +710,7 @@ static HashArgs make_args(const HashLaunch& h)
     a.code_row0 = h.code_row0;
     a.zero = h.zero;
     a.zero_words = h.zero_words;
+    a.wnorm = h.wnorm;
     return a;
 }
 

@@ -32,6 +32,7 @@ struct Plan {
     size_t off_cand;       // [B*Hq][max_blocks][4][kCandCap/4] candidates (distance << 16 | block offset)
     size_t off_part_ml;    // [B*Hq][max_splits] {max, sum} of each attention split
     size_t off_part_acc;   // [B*Hq][max_splits][128] weighted value sums of each split
+    size_t off_wnorm;      // [Hkv][L] norms of the second hash layer's rows (bulk hashing on the matrix cores)
     size_t total_bytes;
 };
 
@@ -114,6 +115,7 @@ struct HashLaunch {
     int64_t code_row0;
     uint32_t* zero;           // if set: zero[xhead * zero_words ...) is cleared by the head's first tile
     int zero_words;
+    float* wnorm;             // [weight heads][L] floats of scratch for the matrix-core path, or null
 };
 int launch_hash(spotlight_ctx* ctx, const HashLaunch& a, int stage);
 // Two hash jobs; one launch when both hash a single vector per head with the same network shape.

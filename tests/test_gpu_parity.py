@@ -191,3 +191,46 @@ def test_out_of_range_indices_are_skipped():
         assert float((got - want).abs().max()) <= ATTN_TOL
     finally:
         c.close()
+
+
+def test_bulk_hash_on_matrix_cores_equals_the_binary32_kernel_and_the_oracle():
+    """Bulk hashing runs its second layer on the matrix cores and recomputes outputs too close to
+    zero with the defined binary32 chain.  Rows built to stress that: zeros (every output exactly
+    0: the whole tile goes to the recomputation), tiny and huge magnitudes, a NaN and an infinity."""
+    import os
+    cfg = C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=40000 + 19, topk=64, needles=0)
+    c = Case(cfg)
+    try:
+        K = c.K
+        K[0, 0, 64:160] = 0                                   # three tiles of zero rows
+        K[0, 1, 1000:1040] *= 1e-30
+        K[0, 1, 2000:2040] *= 1e18
+        K[0, 0, 3000, 5] = float("nan")
+        K[0, 1, 3001, 7] = float("inf")
+        c.hK = K.cpu()
+        n = cfg.n_tokens
+        c.codes.fill_(0)
+        c.ctx.hash_keys(K, *c.weights, 0, n, c.codes)         # matrix-core path (bf16 weights, hidden 256)
+        got = c.codes.clone()
+        os.environ["SPOTLIGHT_NO_MFMA"] = "1"
+        try:
+            c.codes.fill_(0)
+            c.ctx.hash_keys(K, *c.weights, 0, n, c.codes)     # all-binary32 kernel
+        finally:
+            del os.environ["SPOTLIGHT_NO_MFMA"]
+        assert torch.equal(got, c.codes)
+        want = c.oracle_codes(0, 6000)                        # the stressed rows and their surroundings
+        assert torch.equal(got.cpu()[:, :, :6000], want[:, :, :6000])
+        # a second layer of zeros for head 0: every output is exactly 0, no sign can be certified, every
+        # tile of that head overflows its list and is recomputed whole
+        w1, b1, w2 = (t.clone() for t in c.weights)
+        w2[0] = 0
+        c.codes.fill_(-1)
+        c.ctx.hash_keys(K, w1, b1, w2, 0, n, c.codes)
+        assert int(c.codes[:, 0, :n].abs().max()) == 0       # sign(0) is bit 0
+        hw = tuple(t.cpu() for t in (w1, b1, w2))
+        want2 = torch.zeros_like(want)
+        oracle.hash_keys(c.hK, *hw, cfg.code_bits, 0, 3000, want2)
+        assert torch.equal(c.codes.cpu()[:, :, :3000], want2[:, :, :3000])
+    finally:
+        c.close()
