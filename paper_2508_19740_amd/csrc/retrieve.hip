@@ -343,7 +343,8 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
 // ------------------------------------------------------------------------------------ select
 constexpr int kSelThreads = 128;  // one thread per 32 tokens of the block
 
-template <int W>
+// FORCED: the call has sink / local tokens (otherwise that code is compiled out).
+template <int W, bool FORCED>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const uint32_t* __restrict__ codes, const uint32_t* __restrict__ qcode, const uint32_t* __restrict__ gcum,
     const uint32_t* __restrict__ blockcum, const BlockMeta* __restrict__ blockmeta, const uint32_t* __restrict__ cand,
@@ -425,8 +426,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const int64_t t_begin = static_cast<int64_t>(blk) * kTPB;
     const int n_blk = static_cast<int>(min(static_cast<int64_t>(kTPB), n_tokens - t_begin));
     // forced tokens of this block, as offsets into it: [0, sink_end) and [local_off, n_blk)
-    const uint32_t sink_end = static_cast<uint32_t>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), n_sink - t_begin)));
-    const uint32_t local_off = static_cast<uint32_t>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), local_begin - t_begin)));
+    const uint32_t sink_end = !FORCED ? 0u :
+        static_cast<uint32_t>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), n_sink - t_begin)));
+    const uint32_t local_off = !FORCED ? static_cast<uint32_t>(n_blk) :
+        static_cast<uint32_t>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), local_begin - t_begin)));
     bool listed = T <= meta.bound;
 #pragma unroll
     for (int s = 0; s < SUB; ++s) listed = listed && meta.count[s] != kWaveFull;
@@ -437,7 +440,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
             for (int h = 0; h < PER; ++h) {
                 if (h * kSelThreads + tid < static_cast<int>(meta.count[s])) {
                     const uint32_t off = ce[s][h] & (kTPB - 1);
-                    const uint32_t d = (off < sink_end || off >= local_off) ? 0u : ce[s][h] >> 16;   // forced: bin 0
+                    const uint32_t d = (FORCED && (off < sink_end || off >= local_off)) ? 0u : ce[s][h] >> 16;   // forced: bin 0
                     if (d < T) atomicOr(&lt_bits[off >> 5], 1u << (off & 31));
                     else if (d == T) atomicOr(&eq_bits[off >> 5], 1u << (off & 31));
                 }
@@ -456,13 +459,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
             uint32_t d = 1;
 #pragma unroll
             for (int w = 0; w < W; ++w) d += popc(kw[w] ^ qc[w]);
-            if (static_cast<uint32_t>(off) < sink_end || static_cast<uint32_t>(off) >= local_off) d = 0;
+            if (FORCED && (static_cast<uint32_t>(off) < sink_end || static_cast<uint32_t>(off) >= local_off)) d = 0;
             if (d < T) atomicOr(&lt_bits[off >> 5], 1u << (off & 31));
             else if (d == T) atomicOr(&eq_bits[off >> 5], 1u << (off & 31));
         }
     }
     // forced tokens are in bin 0 whether or not a list names them: marked by position
-    if (sink_end > 0 || local_off < static_cast<uint32_t>(n_blk)) {
+    if (FORCED && (sink_end > 0 || local_off < static_cast<uint32_t>(n_blk))) {
         uint32_t m = 0;
         for (int bit = 0; bit < 32; ++bit) {
             const uint32_t off = static_cast<uint32_t>(tid) * 32 + bit;
@@ -593,7 +596,10 @@ int launch_w(spotlight_ctx* ctx, const RetrieveArgs& a)
     {
         StageTimer timer(ctx, SPOTLIGHT_STAGE_SELECT);
         dim3 grid(static_cast<unsigned>(a.nblk), static_cast<unsigned>(BH));
-        hipLaunchKernelGGL(select_kernel<W>, grid, dim3(kSelThreads), 0, ctx->stream, a.codes, qcode,
+        const bool forced = a.n_sink > 0 || a.local_begin < a.n_tokens;
+        auto kern = select_kernel<W, false>;
+        if (forced) kern = select_kernel<W, true>;
+        hipLaunchKernelGGL(kern, grid, dim3(kSelThreads), 0, ctx->stream, a.codes, qcode,
                            reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_gcum),
                            reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_blockcum),
                            reinterpret_cast<const BlockMeta*>(ctx->workspace + p.off_blockmeta),
