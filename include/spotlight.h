@@ -106,8 +106,11 @@ const char *spotlight_strerror(int rc);
  * codes into the code cache: the append of a decode step (n_new = 1) or the bulk build after
  * prefill.  Eq. 5-6 (Eq. 4 if hidden == 0), then bit-packing: hash output c*W + j of a key lands
  * in word j, bit 31 - c (appendix "Bit-Packing CUDA Kernel").  sign(y) is the bit (y > 0).
- * The arithmetic is IEEE binary32 with one fused multiply-add chain per output in increasing
- * index order, so codes do not depend on launch shape.
+ * The codes are those of IEEE binary32 arithmetic with one fused multiply-add chain per output
+ * in increasing index order, so they do not depend on launch shape.  (With bfloat16 weights a
+ * bulk call evaluates the second layer on the matrix cores and recomputes, with that chain, every
+ * output whose sign the matrix-core result does not settle: same bits.  Setting
+ * SPOTLIGHT_NO_MFMA in the environment keeps everything on the chain.)
  *
  *   K      [B, Hkv, Nmax, d]  kv_dtype   read rows t0 .. t0+n_new-1 of every head
  *   codes  [B, Hkv, Nmax, W]  uint32     those rows written, all others untouched
