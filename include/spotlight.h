@@ -61,7 +61,7 @@ typedef struct {
     int32_t n_q_heads;    /* Hq >= 1, multiple of n_kv_heads, Hq / Hkv <= 8              */
     int32_t n_kv_heads;   /* Hkv >= 1                                                    */
     int32_t head_dim;     /* d; only 128 is supported                                    */
-    int32_t code_bits;    /* L; multiple of 32 in [32, 512]                              */
+    int32_t code_bits;    /* L; multiple of 32 in [32, 512], or 1024 (then Hq / Hkv <= 2)   */
     int32_t hidden;       /* h in [0, 4096]; 0 selects the linear hash sign(xR), Eq. 4   */
     int64_t max_tokens;   /* Nmax: token capacity = row stride of K, V and codes         */
     int32_t max_topk;     /* largest k any call will pass, 1 <= max_topk <= max_tokens   */

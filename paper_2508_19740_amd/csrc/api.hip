@@ -14,7 +14,7 @@ int make_plan(const spotlight_config* c, Plan* p)
     if (!c) return SPOTLIGHT_ERR_INVALID_ARG;
     if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return SPOTLIGHT_ERR_INVALID_ARG;
     if (c->n_q_heads % c->n_kv_heads != 0) return SPOTLIGHT_ERR_INVALID_ARG;
-    if (c->code_bits < 32 || c->code_bits > 512 || c->code_bits % 32 != 0) return SPOTLIGHT_ERR_INVALID_ARG;
+    if (c->code_bits < 32 || c->code_bits > 1024 || c->code_bits % 32 != 0) return SPOTLIGHT_ERR_INVALID_ARG;
     if (c->hidden < 0 || c->hidden > 4096) return SPOTLIGHT_ERR_INVALID_ARG;
     if (c->max_tokens < 1 || c->max_tokens > 0x7fffffffLL) return SPOTLIGHT_ERR_INVALID_ARG;
     if (c->max_topk < 1 || c->max_topk > c->max_tokens) return SPOTLIGHT_ERR_INVALID_ARG;
@@ -24,6 +24,8 @@ int make_plan(const spotlight_config* c, Plan* p)
     if (c->head_dim != kHeadDim) return SPOTLIGHT_ERR_UNSUPPORTED;
     const int G = c->n_q_heads / c->n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return SPOTLIGHT_ERR_UNSUPPORTED;
+    // code lengths: every multiple of 32 up to 512 bits, and 1024 bits with at most two query heads per kv head
+    if (c->code_bits > 512 && (c->code_bits != 1024 || G > 2)) return SPOTLIGHT_ERR_UNSUPPORTED;
     if (c->hidden % 8 != 0) return SPOTLIGHT_ERR_UNSUPPORTED;
     if (static_cast<int64_t>(c->batch) * c->n_q_heads > 65535) return SPOTLIGHT_ERR_UNSUPPORTED;
 

@@ -74,8 +74,8 @@ __device__ __forceinline__ void load_key(const char* __restrict__ base, uint32_t
     }
 }
 
-// Sum of x over the LPK (1, 2 or 4) adjacent lanes that share a key: data-parallel-primitive moves
-// within a group of four lanes, no LDS traffic.
+// Sum of x over the LPK (1, 2, 4 or 8) adjacent lanes that share a key: data-parallel-primitive
+// moves within a group of four lanes, then between the two fours of a group of eight; no LDS traffic.
 template <int LPK>
 __device__ __forceinline__ uint32_t add_across_key(uint32_t x)
 {
@@ -83,7 +83,9 @@ __device__ __forceinline__ uint32_t add_across_key(uint32_t x)
         x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0xB1, 0xf, 0xf, true));
     if constexpr (LPK >= 4)   // lanes 2 3 0 1
         x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x4E, 0xf, 0xf, true));
-    static_assert(LPK == 1 || LPK == 2 || LPK == 4, "a key spans at most four lanes");
+    if constexpr (LPK >= 8)   // lanes 7 6 5 4 3 2 1 0 (every lane of a four holds that four's sum by now)
+        x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x141, 0xf, 0xf, true));
+    static_assert(LPK == 1 || LPK == 2 || LPK == 4 || LPK == 8, "a key spans at most eight lanes");
     return x;
 }
 
@@ -115,8 +117,8 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
     constexpr int L = W * 32;
     constexpr int BINS = L + 2;            // bin 0: forced tokens; bin d + 1: distance d
     constexpr int CH = (BINS + 63) / 64;   // bins per lane in the scan
-    // lanes per key: 16 bytes per lane when the code is 16, 32 or 64 bytes, else one lane per key
-    constexpr int LPK = (W == 4 || W == 8 || W == 16) ? W / 4 : 1;
+    // lanes per key: 16 bytes per lane when the code is 16, 32, 64 or 128 bytes, else one lane per key
+    constexpr int LPK = (W == 4 || W == 8 || W == 16 || W == 32) ? W / 4 : 1;
     constexpr int CWL = W / LPK;           // code words per lane
     constexpr int SLOTS = kKPT * LPK;      // load instructions per thread and task
     constexpr int KPS = kThreads / LPK;    // keys per slot
@@ -586,8 +588,13 @@ int launch_w(spotlight_ctx* ctx, const RetrieveArgs& a)
         switch (p.G) {
         case 1: rc = launch_score_wg<W, 1>(ctx, a); break;
         case 2: rc = launch_score_wg<W, 2>(ctx, a); break;
-        case 4: rc = launch_score_wg<W, 4>(ctx, a); break;
-        case 8: rc = launch_score_wg<W, 8>(ctx, a); break;
+        case 4:
+            // 1024-bit codes: the histograms of more than two heads do not fit in LDS
+            if constexpr (W <= 16) { rc = launch_score_wg<W, 4>(ctx, a); break; }
+            return SPOTLIGHT_ERR_UNSUPPORTED;
+        case 8:
+            if constexpr (W <= 16) { rc = launch_score_wg<W, 8>(ctx, a); break; }
+            return SPOTLIGHT_ERR_UNSUPPORTED;
         default: return SPOTLIGHT_ERR_UNSUPPORTED;
         }
         if (rc != SPOTLIGHT_OK) return rc;
@@ -647,6 +654,7 @@ int launch_retrieve(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens,
     case 14: return launch_w<14>(ctx, a);
     case 15: return launch_w<15>(ctx, a);
     case 16: return launch_w<16>(ctx, a);
+    case 32: return launch_w<32>(ctx, a);
     default: return SPOTLIGHT_ERR_UNSUPPORTED;
     }
 }

@@ -56,7 +56,9 @@ def test_validate_config_accepts_the_five_workloads():
     (dict(n_q_heads=30, n_kv_heads=8), sp.ERR_INVALID_ARG),      # not a multiple
     (dict(code_bits=100), sp.ERR_INVALID_ARG),
     (dict(code_bits=0), sp.ERR_INVALID_ARG),
-    (dict(code_bits=544), sp.ERR_INVALID_ARG),
+    (dict(code_bits=1056), sp.ERR_INVALID_ARG),
+    (dict(code_bits=544), sp.ERR_UNSUPPORTED),                   # above 512 only 1024 bits
+    (dict(code_bits=1024, n_q_heads=32, n_kv_heads=8), sp.ERR_UNSUPPORTED),   # 1024 bits: at most 2 heads per group
     (dict(hidden=-8), sp.ERR_INVALID_ARG),
     (dict(max_tokens=0), sp.ERR_INVALID_ARG),
     (dict(max_topk=0), sp.ERR_INVALID_ARG),

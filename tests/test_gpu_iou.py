@@ -55,4 +55,5 @@ def test_iou_at_64k_tokens():
           "chance", round(chance, 4))
     assert iou["lsh_rot_128"] > 5 * chance
     assert iou["lsh_rot_512"] > iou["lsh_rot_128"] + 0.05
+    assert iou["lsh_rot_1024"] > iou["lsh_rot_512"] + 0.03
     assert iou["lsh_gauss_128"] > 5 * chance

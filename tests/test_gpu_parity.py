@@ -23,6 +23,9 @@ SMALL = {
     "lin_128": C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=2049, topk=50, hidden=0, needles=2),
     "lin_512_rot": C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=4500, topk=90, hidden=0, code_bits=512,
                                   lsh_init="rotation", needles=2),
+    "lin_1024_rot": C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=4500, topk=90, hidden=0, code_bits=1024,
+                                   lsh_init="rotation", needles=2),
+    "mlp_1024_g2": C["C2"].scaled(n_q_heads=2, n_kv_heads=1, n_tokens=4097, topk=70, hidden=128, code_bits=1024, needles=2),
     "odd_words": C["C2"].scaled(n_q_heads=2, n_kv_heads=1, n_tokens=1500, topk=33, code_bits=96, hidden=64, needles=2),
     "one_word": C["C1"].scaled(n_tokens=1300, topk=200, code_bits=32, hidden=8, needles=2),
     "f32_kv_bf16_w": C["C1"].scaled(n_tokens=777, topk=77, weight_dtype="bf16", needles=2),

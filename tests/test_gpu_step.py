@@ -19,6 +19,8 @@ SMALL = {
     "c5_512": C["C5-512"].scaled(batch=1, n_q_heads=2, n_kv_heads=2, n_tokens=3000 + 5, topk=100, needles=2, extra_tokens=3),
     "lin_128": C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=2049, topk=90, hidden=0, needles=2),
     "odd_words": C["C2"].scaled(n_q_heads=2, n_kv_heads=1, n_tokens=1500, topk=133, code_bits=96, hidden=64, needles=2),
+    "lin_1024_rot": C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=4500, topk=90, hidden=0, code_bits=1024,
+                                   lsh_init="rotation", needles=2),
     "block_edge": C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=3 * 4096, topk=200, needles=2),
     "g8": C["C4"].scaled(batch=1, n_q_heads=8, n_kv_heads=1, n_tokens=4200, topk=100, code_bits=128, hidden=256, needles=1),
 }

@@ -80,6 +80,7 @@ BASE = wl.CONFIGS["C2"].scaled(n_q_heads=8, n_kv_heads=8, n_tokens=4096, topk=82
 VARIANTS = {
     "lsh_rot_128": BASE.scaled(hidden=0, code_bits=128, lsh_init="rotation"),
     "lsh_rot_512": BASE.scaled(hidden=0, code_bits=512, lsh_init="rotation"),
+    "lsh_rot_1024": BASE.scaled(hidden=0, code_bits=1024, lsh_init="rotation"),
     "lsh_gauss_128": BASE.scaled(hidden=0, code_bits=128),
     "mlp_untrained_128": BASE.scaled(hidden=256, code_bits=128),
 }
@@ -92,5 +93,6 @@ def test_iou_shape_on_the_cone_workload():
           "chance", round(chance, 4))
     assert iou["lsh_rot_128"] > 5 * chance                   # hashing retrieves far better than chance
     assert iou["lsh_rot_512"] > iou["lsh_rot_128"] + 0.05    # longer codes retrieve better (Fig. 2a's axis)
+    assert iou["lsh_rot_1024"] > iou["lsh_rot_512"] + 0.03
     assert iou["lsh_gauss_128"] > 5 * chance
     assert 0.0 <= iou["mlp_untrained_128"] <= 1.0            # untrained MLP: reported, no claim
