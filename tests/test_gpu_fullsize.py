@@ -91,6 +91,42 @@ def check_retrieval_on_synthetic_codes(big, n_tokens=None):
     return idx
 
 
+def check_decode_step_on_synthetic_codes(big, n_sink=4, n_local=64, attn_every=1):
+    """Every head: the one-call step (appended key hashed into generated codes, forced sink / local
+    tokens, attention) against the oracle's single steps on the same codes (attention on every
+    attn_every-th head)."""
+    c = big.cfg
+    n = c.n_tokens
+    G = c.group
+    dcodes = big.synthetic_codes()
+    idx, out = big.ctx.decode_step(big.q, big.K, big.V, *big.weights, dcodes, n, c.topk, n_sink, n_local)
+    idx, out = idx.cpu(), out.cpu()
+    ar = torch.arange(c.topk, dtype=torch.int32)
+    worst = 0.0
+    for b in range(c.batch):
+        for hk in range(c.n_kv_heads):
+            hc = big.w.synthetic_codes(b, hk, 0, n, "cpu").contiguous()
+            # the appended key's code, by the oracle from the generator's K row
+            krow = big.w.kv_rows("K", b, hk, n - 1, 1, "cpu")
+            _, new_code = oracle.hash_rows(krow.contiguous(), *big.head_weights(hk), c.code_bits)
+            hc[n - 1] = new_code[0]
+            assert torch.equal(dcodes[b, hk, n - 1].cpu(), new_code[0]), (b, hk)
+            for g in range(G):
+                hq = hk * G + g
+                _, qc = oracle.hash_rows(big.w.q[b, hq:hq + 1].contiguous(), *big.head_weights(hk), c.code_bits)
+                dist = oracle.hamming(qc[0].contiguous(), hc)
+                want = oracle.topk_forced(dist, c.topk, n_sink, n_local)
+                assert torch.equal(idx[b, hq], want), (b, hq)
+                if (b * c.n_q_heads + hq) % attn_every:
+                    continue
+                sel = want.long().to(DEV)
+                Ks = big.K[b, hk].index_select(0, sel).cpu()
+                Vs = big.V[b, hk].index_select(0, sel).cpu()
+                o = oracle.sparse_attention(big.w.q[b, hq].contiguous(), Ks, Vs, ar, big.scale)
+                worst = max(worst, float((out[b, hq] - o).abs().max()))
+    assert worst <= ATTN_TOL, worst
+
+
 def check_attention_all_heads(big, idx_host):
     """Every head: GPU attention over idx against the oracle on the gathered rows."""
     c = big.cfg
@@ -151,6 +187,7 @@ def test_c3_512k_tokens():
         idx = check_sampled_heads_real_chain(big, [(0, 5), (0, 31)])
         check_attention_all_heads(big, idx)
         check_retrieval_on_synthetic_codes(big)
+        check_decode_step_on_synthetic_codes(big)
     finally:
         big.close()
 
@@ -161,6 +198,7 @@ def test_c4_gqa_batch16():
         idx = check_sampled_heads_real_chain(big, [(0, 0), (9, 3), (15, 7)])
         check_attention_all_heads(big, idx)
         check_retrieval_on_synthetic_codes(big)
+        check_decode_step_on_synthetic_codes(big, attn_every=7)
     finally:
         big.close()
 
