@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="C3", help="C1 | C2 | C3 | C4 | C5-128 | C5-512")
     ap.add_argument("--layers", type=int, default=0, help="independent layers to rotate over (0 = auto)")
+    ap.add_argument("--code-bits", type=int, default=0, help="override the workload's code length L")
+    ap.add_argument("--hidden", type=int, default=-1, help="override the hash MLP's hidden width (0 = linear hash sign(xR))")
+    ap.add_argument("--lsh-init", default="", help="linear hash only: gaussian | rotation")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=2, help="heads in the oracle's timed sample")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -61,6 +64,16 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = wl.CONFIGS[args.config]
+    variant = ""
+    if args.code_bits:
+        cfg = cfg.scaled(code_bits=args.code_bits)
+        variant += f", L={args.code_bits}"
+    if args.hidden >= 0:
+        cfg = cfg.scaled(hidden=args.hidden)
+        variant += f", hidden={args.hidden}"
+    if args.lsh_init:
+        cfg = cfg.scaled(lsh_init=args.lsh_init)
+        variant += f", {args.lsh_init} LSH"
     B, Hq, Hkv, N, L, W, k, d = (cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_tokens, cfg.code_bits,
                                  cfg.words, cfg.topk, cfg.head_dim)
     esz = 2 if cfg.kv_dtype == "bf16" else 4
@@ -88,7 +101,7 @@ def main():
             "K": w.materialize("K", dev),
             "V": w.materialize("V", dev),
             "q": w.q.to(dev),
-            "weights": tuple(t.to(dev) for t in w.hash_weights()),
+            "weights": tuple(None if t is None else t.to(dev) for t in w.hash_weights()),
             "codes": torch.zeros(B, Hkv, cfg.max_tokens, W, dtype=torch.int32, device=dev),
             "idx": torch.empty(B, Hq, k, dtype=torch.int32, device=dev),
             "out": torch.empty(B, Hq, d, dtype=torch.float32, device=dev),
@@ -233,7 +246,8 @@ def main():
     }
 
     result = {
-        "metric": "retrieval_us_512k_tokens_32_heads" if args.config == "C3" else f"retrieval_us_{args.config}",
+        "metric": ("retrieval_us_512k_tokens_32_heads" if args.config == "C3" else f"retrieval_us_{args.config}")
+                  + (f" [variant{variant}]" if variant else ""),
         "value": round(retrieve_us, 2),
         "unit": "us",
         "n_gpus": 1,
