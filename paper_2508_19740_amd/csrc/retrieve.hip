@@ -127,6 +127,7 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
     __shared__ uint32_t cum[G * BINS];     // this block's histogram, then its cumulative form
     __shared__ uint32_t gacc[G * BINS];    // cumulative histogram summed over this run of tasks
     __shared__ uint32_t s_thi[G];
+    __shared__ uint32_t escr[kThreads / 64][kKPT / 2][64];   // per-lane copy of one head's packed distances
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rep = (tid / LPK) & (R - 1);   // the lanes of one key never record the same slot
@@ -214,7 +215,7 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int i = 0; i < kKPT / 2; ++i) dv[g][i] = 0xffffffffu;
+            for (int i = 0; i < kKPT / 2; ++i) dv[g][i] = 0x7fff7fffu;   // absent keys: farther than any bound
 
         // A "slot" is one load instruction of the workgroup: KPS = 256 / LPK keys, LPK adjacent lanes
         // per key, 16 bytes per lane (fully coalesced).  The partial distances of a key are added
@@ -313,28 +314,49 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
             }
         }
 
-        // candidate lists, one sub-list per wavefront: positions from ballots, any fixed order
+        // Candidate lists, one sub-list per wavefront, in any fixed order.  Few keys qualify (a few
+        // per cent), so the work is arranged per qualifying key, not per key: a packed 16-bit
+        // subtraction per register marks the keys below the bound in a per-lane bit mask, a wave scan
+        // of the mask populations gives every lane its place in the sub-list, and the lanes then
+        // write their keys one per round (the longest mask of the wave sets the number of rounds).
+        // The distance of the key a round picks comes back from a per-lane copy of the registers in
+        // LDS, since registers cannot be indexed per lane.
+        typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+        typedef uint16_t __attribute__((may_alias)) u16_view;   // halves of the 32-bit words written below
+        static_assert(kKPT == 16, "the bit layout of the mask assumes eight registers of two keys");
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const uint32_t thi = s_thi[g];
+            const uint32_t thi = __builtin_amdgcn_readfirstlane(s_thi[g]);   // a bin: bound on distance + 1
             const int64_t slot = (bh0 + g) * a.max_blocks + blk;
             uint32_t* cl = a.cand + (slot * (kThreads / 64) + wave) * kWaveCap;
-            uint32_t run = 0;
+            const u16x2 thi2 = __builtin_bit_cast(u16x2, thi | (thi << 16));
+            uint32_t q = 0;   // bit 7 - r: low key of register r qualifies; bit 23 - r: high key
 #pragma unroll
-            for (int i = 0; i < kKPT; ++i) {
-                const uint32_t d = (dv[g][i >> 1] >> ((i & 1) * 16)) & 0xffffu;
-                const bool p = d < thi;   // bin d + 1 <= bound (thi is a bin; absent keys hold 0xffff)
-                const unsigned long long m = __ballot(p);
-                if (p) {
-                    const uint32_t at = run + __builtin_popcountll(m & ((1ull << lane) - 1ull));
+            for (int r = 0; r < kKPT / 2; ++r) {
+                // d - thi in 16 bits: bit 15 set exactly when d < thi (d <= 0x7fff, thi <= L + 1)
+                const uint32_t t = __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2, dv[g][r]) - thi2);
+                q = (q << 1) | ((t >> 15) & 0x00010001u);
+                escr[wave][r][lane] = dv[g][r];
+            }
+            const uint32_t mine = popc(q);
+            const uint32_t incl = wave_inclusive_scan(mine);
+            const uint32_t total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(incl), 63));
+            uint32_t at = incl - mine;
+            while (__ballot(q != 0)) {
+                if (q) {
+                    const int bit = __builtin_ctz(q);
+                    q &= q - 1;
+                    const int r = 7 - (bit & 15), half = bit >> 4;
+                    const uint32_t d = reinterpret_cast<const u16_view*>(&escr[wave][r][lane])[half];
+                    const int j = 2 * r + half;   // index among the keys this lane owns
                     if (at < static_cast<uint32_t>(kWaveCap))
-                        cl[at] = (d << 16) + (0x10000u | static_cast<uint32_t>((i * LPK + sub) * KPS + kq));   // entry: bin << 16 | offset
+                        cl[at] = (d << 16) + (0x10000u | static_cast<uint32_t>((j * LPK + sub) * KPS + kq));   // bin << 16 | offset
+                    ++at;
                 }
-                run += __builtin_popcountll(m);
             }
             if (lane == 0) {
                 BlockMeta* bm = a.blockmeta + slot;
-                bm->count[wave] = run < static_cast<uint32_t>(kWaveFull) ? static_cast<uint8_t>(run) : static_cast<uint8_t>(kWaveFull);
+                bm->count[wave] = total < static_cast<uint32_t>(kWaveFull) ? static_cast<uint8_t>(total) : static_cast<uint8_t>(kWaveFull);
                 if (wave == 0) bm->bound = thi;
             }
         }
@@ -542,9 +564,13 @@ int launch_score_wg(spotlight_ctx* ctx, const RetrieveArgs& a)
     constexpr int BINS = W * 32 + 2;
     // histogram replicas: 8 if they fit in 32 KB of LDS (more did not make the LDS atomics faster
     // and make the per-block fold and re-zero slower), fewer for wide codes and big groups
+    // and so that everything (replicas, two more histograms, 8 KB of emission scratch) stays under 64 KB
     constexpr int kCap = 32768;
-    constexpr int R = (G * BINS * 8 * 4 <= kCap) ? 8 : (G * BINS * 4 * 4 <= kCap) ? 4
-                    : (G * BINS * 2 * 4 <= kCap) ? 2 : 1;
+    constexpr int kRest = G * BINS * 2 * 4 + 8192 + 256;
+    constexpr int R = (G * BINS * 8 * 4 <= kCap && G * BINS * 8 * 4 + kRest <= 65536) ? 8
+                    : (G * BINS * 4 * 4 <= kCap && G * BINS * 4 * 4 + kRest <= 65536) ? 4
+                    : (G * BINS * 2 * 4 <= kCap && G * BINS * 2 * 4 + kRest <= 65536) ? 2 : 1;
+    static_assert(G * BINS * R * 4 + kRest <= 65536, "LDS of the score kernel");
     auto kern = score_kernel<W, G, R>;
     // persistent grid: as many workgroups as the chip holds at once
     static int resident = 0;  // per instantiation; the library drives one kind of device
