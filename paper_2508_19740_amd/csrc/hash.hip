@@ -494,38 +494,10 @@ __global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashVecArgs jobs)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool second = static_cast<int>(blockIdx.x) >= jobs.n_first;   // uniform over the workgroup
-    // field by field, so that both jobs' arguments are fetched at once and selected in registers
-    // (indexing the argument block with `second` costs a chain of dependent scalar loads)
-    HashArgs a;
-    {
-        const HashArgs &j0 = jobs.job[0], &j1 = jobs.job[1];
-        a.x = second ? j1.x : j0.x;
-        a.x_head_stride = second ? j1.x_head_stride : j0.x_head_stride;
-        a.x_row0 = second ? j1.x_row0 : j0.x_row0;
-        a.n_rows = 1;
-        a.heads_per_batch = second ? j1.heads_per_batch : j0.heads_per_batch;
-        a.group = second ? j1.group : j0.group;
-        a.n_wheads = second ? j1.n_wheads : j0.n_wheads;
-        a.w1 = second ? j1.w1 : j0.w1;
-        a.b1 = second ? j1.b1 : j0.b1;
-        a.w2 = second ? j1.w2 : j0.w2;
-        a.hidden = j0.hidden;   // one launch = one network shape
-        a.L = j0.L;
-        a.W = j0.W;
-        a.codes = second ? j1.codes : j0.codes;
-        a.code_head_stride = second ? j1.code_head_stride : j0.code_head_stride;
-        a.code_row0 = second ? j1.code_row0 : j0.code_row0;
-        a.zero = second ? j1.zero : j0.zero;
-        a.zero_words = second ? j1.zero_words : j0.zero_words;
-        a.wnorm = nullptr;
-    }
+    const HashArgs& a = jobs.job[second ? 1 : 0];
     const int xhead = static_cast<int>(blockIdx.x) - (second ? jobs.n_first : 0);
     const int whead = (xhead % a.heads_per_batch) / a.group;
     const XT* x = static_cast<const XT*>(a.x) + xhead * a.x_head_stride + a.x_row0 * kHeadDim;
-    // x is the same for every lane; hiding that from the compiler makes it use vector loads, which
-    // are issued back to back with the weight loads and return in order (as scalar loads they were
-    // waited for one by one before the first weight load went out)
-    asm volatile("" : "+v"(x));
     const int act_dim = a.hidden > 0 ? a.hidden : kHeadDim;   // multiple of 128
     const int n16 = act_dim / kHeadDim;                        // runs of 128 weights per output row
     const WT* wout = a.hidden > 0 ? static_cast<const WT*>(a.w2) + static_cast<int64_t>(whead) * a.L * a.hidden
@@ -546,9 +518,6 @@ __global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashVecArgs jobs)
     if (a.hidden > 0) {
         const WT* w1 = static_cast<const WT*>(a.w1) + static_cast<int64_t>(whead) * a.hidden * kHeadDim;
         const WT* b1 = static_cast<const WT*>(a.b1) + static_cast<int64_t>(whead) * a.hidden;
-        Raw8<XT> xr[G16];
-#pragma unroll
-        for (int g = 0; g < G16; ++g) load_raw(x + g * 8, xr[g]);
         for (int i = tid; i < a.hidden; i += kThreads) {
             Raw8<WT> w1r[G16];
 #pragma unroll
@@ -557,7 +526,7 @@ __global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashVecArgs jobs)
 #pragma unroll
             for (int g = 0; g < G16; ++g) {
                 float xv[8], wv[8];
-                expand(xr[g], xv);
+                load8(x + g * 8, xv);
                 expand(w1r[g], wv);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) acc = __builtin_fmaf(wv[j], xv[j], acc);
@@ -574,25 +543,17 @@ __global__ __launch_bounds__(kThreads) void hash_vec_kernel(HashVecArgs jobs)
     }
     __syncthreads();
 
-    // 128 terms of one output; the activations come from LDS 32 at a time, ahead of their use (read
-    // four at a time right before use, the chain waited for an LDS round trip every four terms)
     auto run128 = [&](const Raw8<WT> (&r)[G16], const float* h, float y) {
 #pragma unroll
-        for (int g0 = 0; g0 < G16; g0 += 4) {
-            float4 hv[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) hv[q] = reinterpret_cast<const float4*>(h + g0 * 8)[q];
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float wv[8];
-                expand(r[g0 + g], wv);
-                const float4 h0 = hv[2 * g], h1 = hv[2 * g + 1];
-                y = __builtin_fmaf(wv[0], h0.x, y); y = __builtin_fmaf(wv[1], h0.y, y);
-                y = __builtin_fmaf(wv[2], h0.z, y); y = __builtin_fmaf(wv[3], h0.w, y);
-                y = __builtin_fmaf(wv[4], h1.x, y); y = __builtin_fmaf(wv[5], h1.y, y);
-                y = __builtin_fmaf(wv[6], h1.z, y); y = __builtin_fmaf(wv[7], h1.w, y);
-            }
+        for (int g = 0; g < G16; ++g) {
+            float wv[8];
+            expand(r[g], wv);
+            const float4 h0 = reinterpret_cast<const float4*>(h + g * 8)[0];
+            const float4 h1 = reinterpret_cast<const float4*>(h + g * 8)[1];
+            y = __builtin_fmaf(wv[0], h0.x, y); y = __builtin_fmaf(wv[1], h0.y, y);
+            y = __builtin_fmaf(wv[2], h0.z, y); y = __builtin_fmaf(wv[3], h0.w, y);
+            y = __builtin_fmaf(wv[4], h1.x, y); y = __builtin_fmaf(wv[5], h1.y, y);
+            y = __builtin_fmaf(wv[6], h1.z, y); y = __builtin_fmaf(wv[7], h1.w, y);
         }
         return y;
     };
