@@ -194,6 +194,31 @@ def main():
     torch.cuda.synchronize()
     fused_ms_per_step = (time.perf_counter() - t0) * 1e3 / K_steps
 
+    # ... and replayed from HIP graphs, one captured step per layer (the call is five kernel
+    # launches and nothing else).  Only for a fixed context length: a graph freezes n_tokens.
+    graph_ms_per_step = None
+    if not grow:
+        side = torch.cuda.Stream()
+        graphs = []
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            for li in range(n_layers):
+                g = torch.cuda.CUDAGraph()
+                g.capture_begin()
+                fused(li)
+                g.capture_end()
+                graphs.append(g)
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            graphs[i % n_layers].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(K_steps):
+            graphs[i % n_layers].replay()
+        torch.cuda.synchronize()
+        graph_ms_per_step = (time.perf_counter() - t0) * 1e3 / K_steps
+        del graphs
+
     # ------------------------------------------------------------------ algorithmic bytes
     # score: every key code read once (L/8 bytes per key per key-value head)
     score_bytes = B * Hkv * N * (L // 8)
@@ -276,6 +301,7 @@ def main():
         "attend_gbps": round(gbps(attend_bytes, attend_us), 1),
         "attend_frac_of_hbm_peak": round(gbps(attend_bytes, attend_us) / HBM_PEAK_GBPS, 4),
         "decode_step_one_call_ms": round(fused_ms_per_step, 4),
+        "decode_step_graph_replay_ms": None if graph_ms_per_step is None else round(graph_ms_per_step, 4),
         "kernel_us": {kname: (round(v, 2) if v is not None else None) for kname, v in stage_us.items()},
         "bulk_hash_keys_ms_per_layer": round(bulk_ms, 3),
         "bulk_hash_keys_gflops": round(2.0 * B * Hkv * N * (cfg.hidden * d + L * cfg.hidden if cfg.hidden else L * d)
