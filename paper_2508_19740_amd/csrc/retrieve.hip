@@ -29,8 +29,9 @@
 // Eq. 1 concatenates) use the same machinery: every histogram has one bin below distance 0.  A
 // token is counted in bin 0 if it is forced and in bin distance + 1 otherwise, so forced tokens
 // sort in front of everything else and the selection is "forced tokens, then the nearest of the
-// others", k in all.  The shift costs nothing (the popcount accumulator starts at 1) and only the
-// few blocks that hold forced tokens take the path that looks at token positions.
+// others", k in all.  The shift costs nothing (it is a constant in the LDS address), and only the
+// few blocks that hold forced tokens do extra work: score re-reads their forced tokens and moves
+// them from the bin of their distance to bin 0, select marks them by position.
 #include "internal.h"
 
 #include <type_traits>
@@ -102,15 +103,15 @@ struct ScoreArgs {
     int Hkv, nblk, max_blocks, k, total_tasks, tasks_per_group;
 };
 
-// Persistent workgroups.  A task is one (batch * kv head, token block); a workgroup takes
-// tasks_per_group CONSECUTIVE tasks, which mostly belong to one head, and keeps that head's
-// cumulative histogram in LDS across them, so the (slow, device-wide) atomics into the head's
-// global histogram happen once per run of tasks instead of once per block.
 // Wavefronts per SIMD the register allocation must leave room for.  The allocator lands on either
 // side of the 128-register line for 256-bit codes with four heads per group depending on unrelated
 // code; four workgroups per compute unit measured 4 % faster than three there.
 constexpr int score_min_waves(int W, int G) { return (W == 8 && G == 4) ? 4 : 1; }
 
+// Persistent workgroups.  A task is one (batch * kv head, token block); a workgroup takes
+// tasks_per_group CONSECUTIVE tasks, which mostly belong to one head, and keeps that head's
+// cumulative histogram in LDS across them, so the (slow, device-wide) atomics into the head's
+// global histogram happen once per run of tasks instead of once per block.
 template <int W, int G, int R>
 __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(ScoreArgs a)
 {
