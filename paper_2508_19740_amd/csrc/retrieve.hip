@@ -478,15 +478,25 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         uint32_t qc[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) qc[w] = qcode[bh * W + w];
-        for (int off = tid; off < n_blk; off += kSelThreads) {
-            uint32_t kw[W];
-            load_key<W>(cbase, static_cast<uint32_t>(off) * (W * 4), kw);
-            uint32_t d = 1;
+        constexpr int U = W <= 8 ? 8 : (W <= 16 ? 4 : 2);   // keys in flight per thread
+        for (int off0 = tid; off0 < n_blk; off0 += kSelThreads * U) {
+            uint32_t kw[U][W];
 #pragma unroll
-            for (int w = 0; w < W; ++w) d += popc(kw[w] ^ qc[w]);
-            if (FORCED && (static_cast<uint32_t>(off) < sink_end || static_cast<uint32_t>(off) >= local_off)) d = 0;
-            if (d < T) atomicOr(&lt_bits[off >> 5], 1u << (off & 31));
-            else if (d == T) atomicOr(&eq_bits[off >> 5], 1u << (off & 31));
+            for (int u = 0; u < U; ++u) {
+                const int off = off0 + u * kSelThreads;
+                if (off < n_blk) load_key<W>(cbase, static_cast<uint32_t>(off) * (W * 4), kw[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int off = off0 + u * kSelThreads;
+                if (off >= n_blk) continue;
+                uint32_t d = 1;
+#pragma unroll
+                for (int w = 0; w < W; ++w) d += popc(kw[u][w] ^ qc[w]);
+                if (FORCED && (static_cast<uint32_t>(off) < sink_end || static_cast<uint32_t>(off) >= local_off)) d = 0;
+                if (d < T) atomicOr(&lt_bits[off >> 5], 1u << (off & 31));
+                else if (d == T) atomicOr(&eq_bits[off >> 5], 1u << (off & 31));
+            }
         }
     }
     // forced tokens are in bin 0 whether or not a list names them: marked by position
