@@ -282,8 +282,9 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u32 xor/popcount (retrieval), f32 (hash MLP, softmax accumulate), bf16 K/V"
-                 if esz == 2 else "u32 xor/popcount (retrieval), f32",
+        "dtype": "u32",
+        "dtype_detail": "u32 xor/popcount and integer counting (retrieval), f32 fma chains (hash MLP), "
+                        + ("bf16 K/V with f32 softmax accumulation (attention)" if esz == 2 else "f32 (attention)"),
         "data": "synthetic",
         "config": {
             "workload": f"{cfg.name}: batch {B}, {Hq} q heads / {Hkv} kv heads, head_dim {d}, "
