@@ -11,7 +11,7 @@ Consecutive steps rotate over several independent "layers" (separate code / K / 
 least 1 GiB of codes in total) so that the 256 MB last-level cache cannot serve the code stream:
 the numbers are HBM numbers, as in a model whose every layer is touched once per token.
 
-Output: ONE JSON line (see README for the fields).
+Output: ONE JSON line.
 """
 from __future__ import annotations
 
