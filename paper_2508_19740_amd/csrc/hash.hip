@@ -239,12 +239,13 @@ __global__ __launch_bounds__(kThreads) void hash_kernel(HashArgs a)
 // Phase 1 is the canonical binary32 chain above (the hidden activations feed a non-linear function,
 // so nothing but the defined arithmetic will do).  Phase 2, Y = H W2^T for a tile of 32 vectors, is
 // a dense contraction and runs as v_mfma_f32_32x32x16_bf16: W2 is bfloat16 as stored, and each
-// activation h is split on the fly into hi + lo (both bfloat16, |h - hi - lo| <= 2^-15 |h|), so
+// activation h is split on the fly into hi + lo (both bfloat16, |h - hi - lo| <= 2^-18 |h|), so
 // the products are exact and two accumulating MFMA passes give y to within
 //     |y_mfma - y_canonical| <= eps * sum_i |W2[j][i] h_i| <= eps * ||W2[j]|| * ||h||
-// with eps = 1.01 * (hidden * (2^-24 + 1.01 * 2^-22) + 2^-15):  hidden roundings of 2^-24 in the
+// with eps = 1.01 * (hidden * (2^-24 + 1.01 * 2^-22) + 2^-17):  hidden roundings of 2^-24 in the
 // canonical chain, at most 2 * hidden additions in the matrix core each assumed to err by at most
-// one unit in the last place of binary32 whatever their order, and the split residue.
+// one unit in the last place of binary32 whatever their order, and the split residue (2^-18, taken
+// as 2^-17).  A fixed 1e-30 on top covers activations so small that a conversion flushes them.
 // The sign of y_mfma is therefore the canonical sign wherever |y_mfma| exceeds that bound; the few
 // outputs that do not (about 0.2 %) are recomputed with the canonical chain from the binary32
 // activations still in LDS.  The codes are identical to the all-binary32 kernel's, bit for bit.
@@ -266,19 +267,20 @@ struct MfmaLds {   // lives in the x tile's LDS once phase 1 is done with it
 };
 static_assert(sizeof(MfmaLds) <= sizeof(float) * kHeadDim * kMfmaTile, "fits in the x tile");
 
-// hi / lo split of 8 activations into two MFMA operands
+// hi / lo split of 8 activations into two MFMA operands: hi = bf16(h) and lo = bf16(h - hi), both
+// rounded to nearest by the packed conversion instruction; h - hi is exact.
 __device__ __forceinline__ void split8(const float (&h)[8], bf16x8_t& hi, bf16x8_t& lo)
 {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
     union { bf16x8_t v; uint32_t u[4]; } a, b;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const uint32_t x0 = __float_as_uint(h[2 * p]), x1 = __float_as_uint(h[2 * p + 1]);
-        const uint32_t h0 = x0 & 0xffff0000u, h1 = x1 & 0xffff0000u;                 // truncated high parts
-        const float r0 = h[2 * p] - __uint_as_float(h0), r1 = h[2 * p + 1] - __uint_as_float(h1);   // exact
-        const uint32_t l0 = (__float_as_uint(r0) + 0x8000u) & 0xffff0000u;          // rounded low parts
-        const uint32_t l1 = (__float_as_uint(r1) + 0x8000u) & 0xffff0000u;
-        a.u[p] = (h0 >> 16) | h1;
-        b.u[p] = (l0 >> 16) | l1;
+        const f32x2_t hv = {h[2 * p], h[2 * p + 1]};
+        const uint32_t hp = __builtin_bit_cast(uint32_t, __builtin_convertvector(hv, bf16x2_t));
+        const f32x2_t rv = {h[2 * p] - __uint_as_float(hp << 16), h[2 * p + 1] - __uint_as_float(hp & 0xffff0000u)};
+        a.u[p] = hp;
+        b.u[p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(rv, bf16x2_t));
     }
     hi = a.v;
     lo = b.v;
@@ -650,7 +652,7 @@ int run_mfma_nbw(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage,
     int tpg = 8;
     while (tpg > 1 && ((tiles + tpg - 1) / tpg) * n_xheads < 4096) tpg /= 2;
     // error bound per unit of ||W2[j]|| * ||h||, see the kernel's header
-    const double eps = 1.01 * (a.hidden * (0x1p-24 + 1.01 * 0x1p-22) + 0x1p-15);
+    const double eps = 1.01 * (a.hidden * (0x1p-24 + 1.01 * 0x1p-22) + 0x1p-17);
     dim3 grid(static_cast<unsigned>((tiles + tpg - 1) / tpg), static_cast<unsigned>(n_xheads));
     StageTimer timer(ctx, stage);
     const int n_out = a.n_wheads * a.L;
