@@ -103,10 +103,10 @@ struct ScoreArgs {
     int Hkv, nblk, max_blocks, k, total_tasks, tasks_per_group;
 };
 
-// Wavefronts per SIMD the register allocation must leave room for.  The allocator lands on either
-// side of the 128-register line for 256-bit codes with four heads per group depending on unrelated
-// code; four workgroups per compute unit measured 4 % faster than three there.
-constexpr int score_min_waves(int W, int G) { return (W == 8 && G == 4) ? 4 : 1; }
+// Wavefronts per SIMD the register allocation must leave room for.  Without the hint the allocator
+// lands on either side of an occupancy step depending on unrelated code (256-bit codes with four
+// heads per group: 4 waves measured 4 % faster than 3; 512-bit codes: 167 or 256 registers).
+constexpr int score_min_waves(int W, int G) { return (W == 8 && G == 4) ? 4 : (W == 16 && G <= 4) ? 3 : 1; }
 
 // Persistent workgroups.  A task is one (batch * kv head, token block); a workgroup takes
 // tasks_per_group CONSECUTIVE tasks, which mostly belong to one head, and keeps that head's
@@ -180,35 +180,44 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
             for (int w = 0; w < CWL; ++w) qc[g][w] = a.qcode[(bh0 + g) * W + sub * CWL + w];
 
         // Forced tokens of this block, as offsets into it: [0, sink_end) and [local_off, n_blk).
-        // Only the first and the last blocks of a head have any.  The main loop below counts them
-        // at the bin of their distance like every other token; here they are moved to bin 0 of the
-        // histogram (the subtraction comes first: the counters wrap and come back).  The candidate
-        // lists keep the distance; select knows the forced tokens by position.
+        // Only the first and the last blocks of a head have any; such a block takes the predicated
+        // path of the main loop, which counts a slot (KPS consecutive tokens) that is forced as a
+        // whole in bin 0 directly.  The forced tokens of the one or two slots that are only partly
+        // forced are counted at the bin of their distance like every other token and moved to bin
+        // 0 here (the subtraction comes first: the counters wrap and come back).  The candidate
+        // lists never hold forced tokens on purpose; select knows them by position.
         const int sink_end = static_cast<int>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), a.n_sink - t_begin)));
-        const int local_off = static_cast<int>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), a.local_begin - t_begin)));
-        if (sink_end > 0 || local_off < n_blk) {
+        const int local_off = max(sink_end,   // windows that meet: every token once
+            static_cast<int>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), a.local_begin - t_begin))));
+        const bool has_forced = sink_end > 0 || local_off < n_blk;
+        // whole slots inside the windows: slots [0, sink_slots) and [local_slot, SLOTS)
+        const int sink_slots = sink_end / KPS, local_slot = (local_off + KPS - 1) / KPS;
+        if (has_forced) {
             const char* blk_base = reinterpret_cast<const char*>(a.codes + (static_cast<int64_t>(bk) * a.Nmax + t_begin) * W);
-            for (int off = tid; off < n_blk; off += kThreads) {
-                if (off >= sink_end && off < local_off) continue;
-                constexpr int CHUNK = W % 4 == 0 ? 4 : 1;   // words per load
-                uint32_t d[G];
+            auto move_to_bin0 = [&](int lo, int hi) {   // fewer than KPS tokens: at most one per thread
+                for (int off = lo + tid; off < hi; off += kThreads) {
+                    constexpr int CHUNK = W % 4 == 0 ? 4 : 1;   // words per load
+                    uint32_t d[G];
 #pragma unroll
-                for (int g = 0; g < G; ++g) d[g] = 0;
+                    for (int g = 0; g < G; ++g) d[g] = 0;
 #pragma unroll 1
-                for (int w0 = 0; w0 < W; w0 += CHUNK) {
-                    uint32_t key[CHUNK];
-                    load_key<CHUNK>(blk_base, static_cast<uint32_t>(off) * (W * 4) + w0 * 4, key);
+                    for (int w0 = 0; w0 < W; w0 += CHUNK) {
+                        uint32_t key[CHUNK];
+                        load_key<CHUNK>(blk_base, static_cast<uint32_t>(off) * (W * 4) + w0 * 4, key);
 #pragma unroll
-                    for (int g = 0; g < G; ++g)
+                        for (int g = 0; g < G; ++g)
 #pragma unroll
-                        for (int w = 0; w < CHUNK; ++w) d[g] += popc(key[w] ^ a.qcode[(bh0 + g) * W + w0 + w]);
+                            for (int w = 0; w < CHUNK; ++w) d[g] += popc(key[w] ^ a.qcode[(bh0 + g) * W + w0 + w]);
+                    }
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        atomicSub(&hist[(g * BINS + 1 + d[g]) * R + rep], 1u);
+                        atomicAdd(&hist[(g * BINS + 0) * R + rep], 1u);
+                    }
                 }
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    atomicSub(&hist[(g * BINS + 1 + d[g]) * R + rep], 1u);
-                    atomicAdd(&hist[(g * BINS + 0) * R + rep], 1u);
-                }
-            }
+            };
+            move_to_bin0(sink_slots * KPS, sink_end);
+            move_to_bin0(local_off, min(n_blk, local_slot * KPS));
         }
 
         // distances of the 16 keys this lane owns, two per register
@@ -242,6 +251,12 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
                     for (int w = 0; w < CWL; ++w) d[g] += popc(kw[u][w] ^ qc[g][w]);
                     d[g] = add_across_key<LPK>(d[g]);
                 }
+                if constexpr (!decltype(full)::value) {
+                    if (sl < sink_slots || sl >= local_slot) {   // a slot of forced tokens (uniform): bin 0
+#pragma unroll
+                        for (int g = 0; g < G; ++g) d[g] = 0xffffffffu;
+                    }
+                }
                 if (valid && (LPK == 1 || sub == sl % LPK)) {
                     const int j = sl / LPK;   // index among the keys this lane owns
 #pragma unroll
@@ -250,15 +265,16 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
                         if constexpr (decltype(full)::value) {   // both halves get written: no mask needed
                             dv[g][j >> 1] = (j & 1) ? (d[g] << 16) | dv[g][j >> 1] : d[g];
                         } else {
-                            if (j & 1) dv[g][j >> 1] = (dv[g][j >> 1] & 0x0000ffffu) | (d[g] << 16);
-                            else dv[g][j >> 1] = (dv[g][j >> 1] & 0xffff0000u) | d[g];
+                            const uint32_t d16 = d[g] & 0x7fffu;   // a forced slot's 0xffffffff: never a candidate
+                            if (j & 1) dv[g][j >> 1] = (dv[g][j >> 1] & 0x0000ffffu) | (d16 << 16);
+                            else dv[g][j >> 1] = (dv[g][j >> 1] & 0xffff0000u) | d16;
                         }
                     }
                 }
             }
         }
         };
-        if (n_blk == kTPB) score_block(std::true_type{});
+        if (n_blk == kTPB && !has_forced) score_block(std::true_type{});
         else score_block(std::false_type{});
 
         __syncthreads();
@@ -274,7 +290,9 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
         for (int i = tid; i < G * BINS * R; i += kThreads) hist[i] = 0;  // ready for the next task
 
         // cumulative histogram per head (one wave per head), and the block-local candidate bound:
-        // the first distance at which about twice the block's fair share of k (plus a little) is reached
+        // the first bin at which about twice the block's fair share of k (plus a little) is reached,
+        // counting only tokens outside the forced windows (bin 0 is not a distance; select places
+        // forced tokens by position and needs no candidates for them)
         const uint32_t want = static_cast<uint32_t>(min(static_cast<int64_t>(n_blk),
             (static_cast<int64_t>(n_blk) * a.k * 2 + a.n_tokens - 1) / a.n_tokens + 32));
         for (int g = wave; g < G; g += kThreads / 64) {
@@ -287,6 +305,9 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
                 v[c] = tot;
             }
             const uint32_t before = wave_inclusive_scan(tot) - tot;
+            const uint32_t c0 = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(v[0])));   // bin 0
+            const uint32_t wantn = min(want, static_cast<uint32_t>(n_blk) - c0);
+            if (lane == 0 && wantn == 0) s_thi[g] = BINS - 1;   // nothing but forced tokens: no candidate either way
             uint32_t prev = before;
 #pragma unroll
             for (int c = 0; c < CH; ++c) {
@@ -295,7 +316,7 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
                     const uint32_t cv = before + v[c];
                     cum[g * BINS + bin] = cv;
                     gacc[g * BINS + bin] += cv;
-                    if (cv >= want && prev < want) s_thi[g] = static_cast<uint32_t>(bin);  // exactly one bin
+                    if (bin > 0 && wantn > 0 && cv - c0 >= wantn && prev - c0 < wantn) s_thi[g] = static_cast<uint32_t>(bin);  // exactly one bin
                     prev = cv;
                 }
             }
@@ -385,6 +406,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __shared__ uint32_t red[2][NW];
     __shared__ uint32_t lt_bits[kSelThreads], eq_bits[kSelThreads];
     __shared__ uint32_t wsum[NW];
+    __shared__ uint16_t dense[kTPB];   // offsets of the selected tokens, for blocks selected almost whole
+    constexpr uint32_t kDenseOutput = 512;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t bh = blockIdx.y;
@@ -488,14 +511,21 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int off = off0 + u * kSelThreads;
-                if (off >= n_blk) continue;
+                const int off = off0 + u * kSelThreads;   // a wavefront holds 64 consecutive offsets
                 uint32_t d = 1;
 #pragma unroll
                 for (int w = 0; w < W; ++w) d += popc(kw[u][w] ^ qc[w]);
                 if (FORCED && (static_cast<uint32_t>(off) < sink_end || static_cast<uint32_t>(off) >= local_off)) d = 0;
-                if (d < T) atomicOr(&lt_bits[off >> 5], 1u << (off & 31));
-                else if (d == T) atomicOr(&eq_bits[off >> 5], 1u << (off & 31));
+                // one bitmap word per 32 lanes, written by one of them (32 lanes OR-ing single bits
+                // into the same LDS word serialise: 85 us for a block that is all below T)
+                const unsigned long long mlt = __ballot(off < n_blk && d < T);
+                const unsigned long long meq = __ballot(off < n_blk && d == T);
+                if ((lane & 31) == 0 && off < n_blk) {
+                    const uint32_t wlt = static_cast<uint32_t>(lane ? mlt >> 32 : mlt);
+                    const uint32_t weq = static_cast<uint32_t>(lane ? meq >> 32 : meq);
+                    if (wlt) atomicOr(&lt_bits[off >> 5], wlt);
+                    if (weq) atomicOr(&eq_bits[off >> 5], weq);
+                }
             }
         }
     }
@@ -528,15 +558,31 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const uint32_t sn = wave_inclusive_scan(cnt);
     if (lane == 63) wsum[wave] = sn;
     __syncthreads();
-    pos += sn - cnt;
-    if (wave == 1) pos += wsum[0];
+    uint32_t local = sn - cnt;                      // place of this thread's first token among the block's
+    if (wave == 1) local += wsum[0];
+    const uint32_t n_sel = wsum[0] + wsum[1];       // tokens this block contributes (own_lt + quota)
     int32_t* op = out_idx + bh * k;
-    const int32_t tok0 = static_cast<int32_t>(t_begin) + tid * 32;
-    while (sel) {
-        const int bit = __builtin_ctz(sel);
-        sel &= sel - 1;
-        if (pos < static_cast<uint32_t>(k)) op[pos] = tok0 + bit;
-        ++pos;
+    if (n_sel <= kDenseOutput) {
+        // the usual case, a few dozen tokens per block: every thread writes its own
+        pos += local;
+        const int32_t tok0 = static_cast<int32_t>(t_begin) + tid * 32;
+        while (sel) {
+            const int bit = __builtin_ctz(sel);
+            sel &= sel - 1;
+            if (pos < static_cast<uint32_t>(k)) op[pos] = tok0 + bit;
+            ++pos;
+        }
+    } else {
+        // a block that is selected almost whole (wide forced windows, k close to N): written thread by
+        // thread, every store instruction touches 64 cache lines; through LDS the stores are contiguous
+        while (sel) {
+            const int bit = __builtin_ctz(sel);
+            sel &= sel - 1;
+            dense[local++] = static_cast<uint16_t>(tid * 32 + bit);
+        }
+        __syncthreads();
+        for (uint32_t i = tid; i < n_sel; i += kSelThreads)
+            if (pos + i < static_cast<uint32_t>(k)) op[pos + i] = static_cast<int32_t>(t_begin) + dense[i];
     }
 }
 
