@@ -501,7 +501,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         uint32_t qc[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) qc[w] = qcode[bh * W + w];
-        constexpr int U = W <= 8 ? 8 : (W <= 16 ? 4 : 2);   // keys in flight per thread
+        constexpr int U = W <= 4 ? 8 : (W <= 8 ? 4 : (W <= 16 ? 2 : 1));   // keys in flight per thread (within 64 registers)
         for (int off0 = tid; off0 < n_blk; off0 += kSelThreads * U) {
             uint32_t kw[U][W];
 #pragma unroll
