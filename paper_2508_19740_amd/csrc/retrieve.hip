@@ -387,27 +387,54 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
 }
 
 // ------------------------------------------------------------------------------------ select
-constexpr int kSelThreads = 128;  // one thread per 32 tokens of the block
+// Workgroup sizes of the select kernel.  Two wavefronts per block (one thread per 32 tokens) have the
+// shorter dependent chain; one wavefront (one thread per 64 tokens) lets twice as many blocks be
+// resident per compute unit, which wins once the grid needs several rounds to pass through the chip.
+constexpr int kSelThreads = 128;
+constexpr int kSelThreadsNarrow = 64;
+constexpr int kSelWideGrid = 256 * 16;   // workgroups of kSelThreads resident on the chip at once
+
+template <int TOK> struct TokenMask { using type = uint32_t; };
+template <> struct TokenMask<64> { using type = uint64_t; };
+__device__ __forceinline__ uint32_t popc_m(uint32_t x) { return static_cast<uint32_t>(__builtin_popcount(x)); }
+__device__ __forceinline__ uint32_t popc_m(uint64_t x) { return static_cast<uint32_t>(__builtin_popcountll(x)); }
+__device__ __forceinline__ int ctz_m(uint32_t x) { return __builtin_ctz(x); }
+__device__ __forceinline__ int ctz_m(uint64_t x) { return __builtin_ctzll(x); }
+__device__ __forceinline__ uint32_t drop_highest(uint32_t x) { return x & ~(0x80000000u >> __builtin_clz(x)); }
+__device__ __forceinline__ uint64_t drop_highest(uint64_t x) { return x & ~(0x8000000000000000ull >> __builtin_clzll(x)); }
+// bits i of a 32-token bitmap word starting at token `first` with first + i < bound
+__device__ __forceinline__ uint32_t bits_below(uint32_t first, uint32_t bound)
+{
+    if (bound <= first) return 0u;
+    const uint32_t n = bound - first;
+    return n >= 32 ? 0xffffffffu : (1u << n) - 1u;
+}
 
 // FORCED: the call has sink / local tokens (otherwise that code is compiled out).
-template <int W, bool FORCED>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(
+template <int W, bool FORCED, int THREADS>
+__global__ __launch_bounds__(THREADS) void select_kernel(
     const uint32_t* __restrict__ codes, const uint32_t* __restrict__ qcode, const uint32_t* __restrict__ gcum,
     const uint32_t* __restrict__ blockcum, const BlockMeta* __restrict__ blockmeta, const uint32_t* __restrict__ cand,
     int32_t* __restrict__ out_idx, int64_t n_tokens, int64_t Nmax, int Hq, int Hkv, int max_blocks, int k,
     int64_t n_sink, int64_t local_begin)
 {
     constexpr int BINS = W * 32 + 2;   // bin 0: forced tokens; bin d + 1: distance d
-    constexpr int NW = kSelThreads / 64;
-    constexpr int SUB = kThreads / 64;               // candidate sub-lists per block
-    constexpr int PER = kWaveCap / kSelThreads;      // sub-list entries per thread (2)
-    static_assert(kTPB / 32 == kSelThreads, "one bitmap word per thread");
+    constexpr int NW = THREADS / 64;
+    constexpr int SUB = kThreads / 64;          // candidate sub-lists per block
+    constexpr int PER = kWaveCap / THREADS;     // sub-list entries per thread
+    constexpr int WORDS = kTPB / 32;            // bitmap words of a block
+    constexpr int TOK = kTPB / THREADS;         // tokens owned by a thread
+    constexpr int WPT = TOK / 32;               // bitmap words owned by a thread
+    static_assert(NW == 1 || NW == 2, "one or two wavefronts");
+    static_assert(TOK == 32 || TOK == 64, "a thread's tokens fit one mask");
+    using mask_t = typename TokenMask<TOK>::type;
+    constexpr uint32_t kDenseOutput = 512;
+    constexpr uint32_t kDenseChunk = 1024;
     __shared__ uint32_t s_T, s_r;
     __shared__ uint32_t red[2][NW];
-    __shared__ uint32_t lt_bits[kSelThreads], eq_bits[kSelThreads];
+    __shared__ uint32_t lt_bits[WORDS], eq_bits[WORDS];
     __shared__ uint32_t wsum[NW];
-    __shared__ uint16_t dense[kTPB];   // offsets of the selected tokens, for blocks selected almost whole
-    constexpr uint32_t kDenseOutput = 512;
+    __shared__ uint16_t dense[kDenseChunk];   // offsets of selected tokens, for blocks selected almost whole
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t bh = blockIdx.y;
@@ -416,7 +443,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const uint32_t* bc = blockcum + bh * max_blocks * BINS;
     const int64_t slot = bh * max_blocks + blk;
     // The candidate entries are fetched before the threshold is known, so that their latency
-    // overlaps the threshold search; the first half of every sub-list (which is all of it unless
+    // overlaps the threshold search; the first THREADS of every sub-list (which is all of it unless
     // the block is unusually dense) even before the sub-list lengths are known.  Entries past a
     // sub-list's length hold whatever the workspace held: they are never looked at.
     uint32_t ce[SUB][PER];
@@ -428,13 +455,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
         for (int h = 1; h < PER; ++h) {
             ce[s][h] = 0;
-            if (meta.count[s] != kWaveFull && h * kSelThreads + tid < static_cast<int>(meta.count[s]))
-                ce[s][h] = cand[(slot * SUB + s) * kWaveCap + h * kSelThreads + tid];
+            if (meta.count[s] != kWaveFull && h * THREADS + tid < static_cast<int>(meta.count[s]))
+                ce[s][h] = cand[(slot * SUB + s) * kWaveCap + h * THREADS + tid];
         }
 
-    lt_bits[tid] = 0;
-    eq_bits[tid] = 0;
-    for (int bin = tid; bin < BINS; bin += kSelThreads) {
+#pragma unroll
+    for (int i = 0; i < WPT; ++i) {
+        lt_bits[i * THREADS + tid] = 0;
+        eq_bits[i * THREADS + tid] = 0;
+    }
+    for (int bin = tid; bin < BINS; bin += THREADS) {
         const uint32_t c = gc[bin];
         const uint32_t p = bin ? gc[bin - 1] : 0u;
         // exactly one bin qualifies for a consistent histogram; the last bin also takes the case "never
@@ -449,7 +479,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 
     // tokens below T and in the tie bucket, in the blocks before this one
     uint32_t lt = 0, eq = 0;
-    for (int j = tid; j < blk; j += kSelThreads) {
+    for (int j = tid; j < blk; j += THREADS) {
         const uint32_t le = bc[static_cast<int64_t>(j) * BINS + T];
         const uint32_t l = T ? bc[static_cast<int64_t>(j) * BINS + T - 1] : 0u;
         lt += l;
@@ -457,10 +487,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     }
     lt = wave_sum(lt);
     eq = wave_sum(eq);
-    if (lane == 0) { red[0][wave] = lt; red[1][wave] = eq; }
-    __syncthreads();
-    lt = red[0][0] + red[0][1];
-    eq = red[1][0] + red[1][1];
+    if constexpr (NW > 1) {
+        if (lane == 0) { red[0][wave] = lt; red[1][wave] = eq; }
+        __syncthreads();
+        lt = red[0][0] + red[0][1];
+        eq = red[1][0] + red[1][1];
+    }
     const uint32_t own_le = bc[static_cast<int64_t>(blk) * BINS + T];
     const uint32_t own_lt = T ? bc[static_cast<int64_t>(blk) * BINS + T - 1] : 0u;
     const uint32_t own_eq = own_le - own_lt;
@@ -486,7 +518,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         for (int s = 0; s < SUB; ++s)
 #pragma unroll
             for (int h = 0; h < PER; ++h) {
-                if (h * kSelThreads + tid < static_cast<int>(meta.count[s])) {
+                if (h * THREADS + tid < static_cast<int>(meta.count[s])) {
                     const uint32_t off = ce[s][h] & (kTPB - 1);
                     const uint32_t d = (FORCED && (off < sink_end || off >= local_off)) ? 0u : ce[s][h] >> 16;   // forced: bin 0
                     if (d < T) atomicOr(&lt_bits[off >> 5], 1u << (off & 31));
@@ -502,16 +534,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
         for (int w = 0; w < W; ++w) qc[w] = qcode[bh * W + w];
         constexpr int U = W <= 4 ? 8 : (W <= 8 ? 4 : (W <= 16 ? 2 : 1));   // keys in flight per thread (within 64 registers)
-        for (int off0 = tid; off0 < n_blk; off0 += kSelThreads * U) {
+        for (int off0 = tid; off0 < n_blk; off0 += THREADS * U) {
             uint32_t kw[U][W];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int off = off0 + u * kSelThreads;
+                const int off = off0 + u * THREADS;
                 if (off < n_blk) load_key<W>(cbase, static_cast<uint32_t>(off) * (W * 4), kw[u]);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int off = off0 + u * kSelThreads;   // a wavefront holds 64 consecutive offsets
+                const int off = off0 + u * THREADS;   // a wavefront holds 64 consecutive offsets
                 uint32_t d = 1;
 #pragma unroll
                 for (int w = 0; w < W; ++w) d += popc(kw[u][w] ^ qc[w]);
@@ -531,58 +563,77 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     }
     // forced tokens are in bin 0 whether or not a list names them: marked by position
     if (FORCED && (sink_end > 0 || local_off < static_cast<uint32_t>(n_blk))) {
-        uint32_t m = 0;
-        for (int bit = 0; bit < 32; ++bit) {
-            const uint32_t off = static_cast<uint32_t>(tid) * 32 + bit;
-            if (off < static_cast<uint32_t>(n_blk) && (off < sink_end || off >= local_off)) m |= 1u << bit;
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) {
+            const int word = i * THREADS + tid;
+            const uint32_t first = static_cast<uint32_t>(word) * 32;
+            const uint32_t m = (bits_below(first, sink_end) | ~bits_below(first, local_off)) &
+                               bits_below(first, static_cast<uint32_t>(n_blk));
+            if (m) atomicOr(T > 0 ? &lt_bits[word] : &eq_bits[word], m);
         }
-        if (m) atomicOr(T > 0 ? &lt_bits[tid] : &eq_bits[tid], m);
     }
     __syncthreads();
 
-    // thread j owns tokens 32j .. 32j+31 of the block
-    const uint32_t lw = lt_bits[tid];
-    uint32_t ew = eq_bits[tid];
-    const uint32_t ecount = popc(ew);
+    // thread j owns tokens TOK*j .. TOK*j + TOK-1 of the block
+    mask_t lw = lt_bits[tid * WPT];
+    mask_t ew = eq_bits[tid * WPT];
+    if constexpr (WPT == 2) {
+        lw |= static_cast<mask_t>(lt_bits[tid * WPT + 1]) << 32;
+        ew |= static_cast<mask_t>(eq_bits[tid * WPT + 1]) << 32;
+    }
+    const uint32_t ecount = popc_m(ew);
     const uint32_t sc = wave_inclusive_scan(ecount);  // tie counts over threads (token order)
-    if (lane == 63) wsum[wave] = sc;
-    __syncthreads();
     uint32_t eq_before = sc - ecount;
-    if (wave == 1) eq_before += wsum[0];
+    if constexpr (NW > 1) {
+        if (lane == 63) wsum[wave] = sc;
+        __syncthreads();
+        if (wave == 1) eq_before += wsum[0];
+        __syncthreads();  // wsum is reused
+    }
     const uint32_t gone = eq_before < quota ? eq_before : quota;  // quota used by earlier threads
     const uint32_t take = (quota - gone) < ecount ? (quota - gone) : ecount;
-    while (static_cast<uint32_t>(popc(ew)) > take) ew &= ~(0x80000000u >> __builtin_clz(ew));  // drop the highest ties
-    uint32_t sel = lw | ew;
-    const uint32_t cnt = popc(sel);
-    __syncthreads();  // wsum is reused
+    while (popc_m(ew) > take) ew = drop_highest(ew);  // drop the highest ties
+    mask_t sel = lw | ew;
+    const uint32_t cnt = popc_m(sel);
     const uint32_t sn = wave_inclusive_scan(cnt);
-    if (lane == 63) wsum[wave] = sn;
-    __syncthreads();
     uint32_t local = sn - cnt;                      // place of this thread's first token among the block's
-    if (wave == 1) local += wsum[0];
-    const uint32_t n_sel = wsum[0] + wsum[1];       // tokens this block contributes (own_lt + quota)
+    uint32_t n_sel;                                 // tokens this block contributes (own_lt + quota)
+    if constexpr (NW > 1) {
+        if (lane == 63) wsum[wave] = sn;
+        __syncthreads();
+        if (wave == 1) local += wsum[0];
+        n_sel = wsum[0] + wsum[1];
+    } else {
+        n_sel = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(sn), 63));
+    }
     int32_t* op = out_idx + bh * k;
     if (n_sel <= kDenseOutput) {
         // the usual case, a few dozen tokens per block: every thread writes its own
         pos += local;
-        const int32_t tok0 = static_cast<int32_t>(t_begin) + tid * 32;
+        const int32_t tok0 = static_cast<int32_t>(t_begin) + tid * TOK;
         while (sel) {
-            const int bit = __builtin_ctz(sel);
+            const int bit = ctz_m(sel);
             sel &= sel - 1;
             if (pos < static_cast<uint32_t>(k)) op[pos] = tok0 + bit;
             ++pos;
         }
     } else {
         // a block that is selected almost whole (wide forced windows, k close to N): written thread by
-        // thread, every store instruction touches 64 cache lines; through LDS the stores are contiguous
-        while (sel) {
-            const int bit = __builtin_ctz(sel);
-            sel &= sel - 1;
-            dense[local++] = static_cast<uint16_t>(tid * 32 + bit);
+        // thread, every store instruction touches 64 cache lines; through LDS, a chunk of the block's
+        // output at a time, the stores are contiguous
+        for (uint32_t base = 0; base < n_sel; base += kDenseChunk) {
+            while (sel && local < base + kDenseChunk) {
+                const int bit = ctz_m(sel);
+                sel &= sel - 1;
+                dense[local - base] = static_cast<uint16_t>(tid * TOK + bit);
+                ++local;
+            }
+            __syncthreads();
+            const uint32_t n_chunk = min(kDenseChunk, n_sel - base);
+            for (uint32_t i = tid; i < n_chunk; i += THREADS)
+                if (pos + base + i < static_cast<uint32_t>(k)) op[pos + base + i] = static_cast<int32_t>(t_begin) + dense[i];
+            __syncthreads();
         }
-        __syncthreads();
-        for (uint32_t i = tid; i < n_sel; i += kSelThreads)
-            if (pos + i < static_cast<uint32_t>(k)) op[pos + i] = static_cast<int32_t>(t_begin) + dense[i];
     }
 }
 
@@ -687,9 +738,13 @@ int launch_w(spotlight_ctx* ctx, const RetrieveArgs& a)
         StageTimer timer(ctx, SPOTLIGHT_STAGE_SELECT);
         dim3 grid(static_cast<unsigned>(a.nblk), static_cast<unsigned>(BH));
         const bool forced = a.n_sink > 0 || a.local_begin < a.n_tokens;
-        auto kern = select_kernel<W, false>;
-        if (forced) kern = select_kernel<W, true>;
-        hipLaunchKernelGGL(kern, grid, dim3(kSelThreads), 0, ctx->stream, a.codes, qcode,
+        // small grids: two wavefronts per block; grids of several rounds: one, twice as many resident
+        const bool narrow = static_cast<int64_t>(a.nblk) * BH > kSelWideGrid;
+        auto kern = select_kernel<W, false, kSelThreads>;
+        if (forced && !narrow) kern = select_kernel<W, true, kSelThreads>;
+        if (!forced && narrow) kern = select_kernel<W, false, kSelThreadsNarrow>;
+        if (forced && narrow) kern = select_kernel<W, true, kSelThreadsNarrow>;
+        hipLaunchKernelGGL(kern, grid, dim3(narrow ? kSelThreadsNarrow : kSelThreads), 0, ctx->stream, a.codes, qcode,
                            reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_gcum),
                            reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_blockcum),
                            reinterpret_cast<const BlockMeta*>(ctx->workspace + p.off_blockmeta),
