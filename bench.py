@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--code-bits", type=int, default=0, help="override the workload's code length L")
     ap.add_argument("--hidden", type=int, default=-1, help="override the hash MLP's hidden width (0 = linear hash sign(xR))")
     ap.add_argument("--lsh-init", default="", help="linear hash only: gaussian | rotation")
+    ap.add_argument("--no-prepack", action="store_true",
+                    help="hash from the weight arrays as stored (no packed copy in the contexts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=2, help="heads in the oracle's timed sample")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -91,7 +93,8 @@ def main():
 
     # ------------------------------------------------------------------ inputs (untimed)
     t_setup = time.time()
-    ctx = sp.Spotlight(B, Hq, Hkv, L, cfg.hidden, cfg.max_tokens, k, kv_dtype=kv_t, weight_dtype=w_t, device=dev)
+    # One context per layer, as a model would hold them: each keeps the packed copy of its layer's
+    # hash weights (spotlight_prepack_weights, made once here, untimed like the weights' upload).
     layers = []
     for li in range(n_layers):
         c = cfg.scaled(seed=cfg.seed + 1000 * li)
@@ -105,20 +108,36 @@ def main():
             "codes": torch.zeros(B, Hkv, cfg.max_tokens, W, dtype=torch.int32, device=dev),
             "idx": torch.empty(B, Hq, k, dtype=torch.int32, device=dev),
             "out": torch.empty(B, Hq, d, dtype=torch.float32, device=dev),
+            "ctx": sp.Spotlight(B, Hq, Hkv, L, cfg.hidden, cfg.max_tokens, k, kv_dtype=kv_t, weight_dtype=w_t, device=dev),
         }
+        if not args.no_prepack:
+            lay["ctx"].prepack_weights(*lay["weights"])
         layers.append(lay)
     torch.cuda.synchronize()
     t_gen = time.time() - t_setup
     # bulk build of the code caches (setup, timed separately)
-    ctx.profile_enable(True)
+    def profile_enable(on):
+        for lay in layers:
+            lay["ctx"].profile_enable(on)
+
+    def profile_read():   # totals over the layers' contexts
+        tot = {name: [0.0, 0] for name in sp.STAGES}
+        for lay in layers:
+            for name, (ms, n) in lay["ctx"].profile_read().items():
+                tot[name][0] += ms
+                tot[name][1] += n
+        return tot
+
+    profile_enable(True)
     for lay in layers:
-        ctx.hash_keys(lay["K"], *lay["weights"], 0, N, lay["codes"])
-    prof = ctx.profile_read()
+        lay["ctx"].hash_keys(lay["K"], *lay["weights"], 0, N, lay["codes"])
+    prof = profile_read()
     bulk_ms = prof["hash_keys"][0] / max(1, prof["hash_keys"][1])
-    ctx.profile_enable(False)
+    profile_enable(False)
 
     def step(i, ev=None):
         lay = layers[i % n_layers]
+        ctx = lay["ctx"]
         n_tok = N
         if grow:                                    # append one key per head, then retrieve over n+1
             j = (i // n_layers) % cfg.extra_tokens
@@ -164,17 +183,17 @@ def main():
 
     # ------------------------------------------------------------------ per-kernel durations
     # Same K steps again with every kernel launch bracketed by HIP events on the library's stream.
-    ctx.profile_enable(True)
+    profile_enable(True)
     stage = {name: [0.0, 0] for name in sp.STAGES}
     done = 0
     while done < K_steps:
         chunk = min(K_steps - done, 512)            # at most 8192 recorded launches between reads
         for i in range(done, done + chunk):
             step(i)
-        for name, (ms, n) in ctx.profile_read().items():
+        for name, (ms, n) in profile_read().items():
             stage[name] = [ms, n]
         done += chunk
-    ctx.profile_enable(False)
+    profile_enable(False)
     stage_us = {name: (ms * 1e3 / n if n else None) for name, (ms, n) in stage.items()}
 
     # ------------------------------------------------------------------ the same step as ONE call
@@ -182,7 +201,7 @@ def main():
     def fused(i):
         lay = layers[i % n_layers]
         n_tok = N + (i // n_layers) % cfg.extra_tokens + 1 if grow else N
-        ctx.decode_step(lay["q"], lay["K"], lay["V"], *lay["weights"], lay["codes"], n_tok, k, 0, 0,
+        lay["ctx"].decode_step(lay["q"], lay["K"], lay["V"], *lay["weights"], lay["codes"], n_tok, k, 0, 0,
                         out_idx=lay["idx"], out=lay["out"])
 
     for i in range(args.warmup):
@@ -291,6 +310,7 @@ def main():
                         f"{N} cached tokens, {L}-bit codes (MLP {d}->{cfg.hidden}->{L}), top-k {k}, "
                         f"{cfg.kv_dtype} K/V",
             "layers_rotated": n_layers,
+            "hash_weights": "as stored" if args.no_prepack else "prepacked once per layer (spotlight_prepack_weights)",
             "step": "append-hash 1 key/head + retrieve_topk + sparse_decode",
         },
         "retrieve_us": {"mean": round(retrieve_us, 2), "median": round(retr_us[K_steps // 2], 2),
@@ -316,7 +336,8 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, layers[0], args.cpu_heads)
 
-    ctx.close()
+    for lay in layers:
+        lay["ctx"].close()
     print(json.dumps(result))
 
 

@@ -89,7 +89,8 @@ size_t spotlight_workspace_bytes(const spotlight_config *cfg);
 
 /* Allocates the context and its device workspace on the current device.  *out is set only on
  * success.  The workspace holds the query codes, per-block distance histograms and candidate
- * lists (about one byte per (query head, token)), and the partial attention results. */
+ * lists (about one byte per (query head, token)), the partial attention results, and room for
+ * one copy of the hash weights (spotlight_prepack_weights). */
 int spotlight_create(spotlight_ctx **out, const spotlight_config *cfg);
 
 /* Waits for the stream, frees the workspace and the context.  NULL is accepted. */
@@ -100,6 +101,20 @@ int spotlight_set_stream(spotlight_ctx *ctx, void *stream);
 
 /* Static text for a return code. */
 const char *spotlight_strerror(int rc);
+
+/*
+ * Optional, for callers whose hash weights stay put (inference): copies the weights into the
+ * context's workspace in the order the kernel that hashes ONE vector per head reads them, so that
+ * its loads are contiguous (the decode-step hashing of Eq. 5-6 for the queries and the appended
+ * key: 28 -> 15 us for 640 vectors of a 128 -> 512 -> 256 network).  Later calls that pass the same
+ * three pointers use the copy; the codes are the same bit for bit.  The copy is made on the
+ * context's stream, in stream order with the calls around it.  It is a snapshot: after changing the
+ * CONTENTS of the arrays call this again (or pass NULL to drop the copy); calls that pass other
+ * pointers read their own arrays.  Hidden widths that are not a multiple of 128 have no such
+ * kernel: the call succeeds and changes nothing.
+ * Errors: INVALID_ARG for a NULL context or missing / misaligned arrays.
+ */
+int spotlight_prepack_weights(spotlight_ctx *ctx, const spotlight_hash_weights *w);
 
 /*
  * Hash the key rows [t0, t0 + n_new) of every (batch, key-value head) and write their packed

@@ -6,6 +6,7 @@ been built; there is no CPU or eager fallback.
 """
 from .binding import (  # noqa: F401
     Spotlight, SpotlightError, Config, HashWeights, make_config, validate_config, workspace_bytes,
-    token_budget, spotlight_hash_keys, spotlight_retrieve_topk, spotlight_sparse_decode, spotlight_decode_step, lib, SYMBOLS,
+    token_budget, spotlight_hash_keys, spotlight_retrieve_topk, spotlight_sparse_decode, spotlight_decode_step,
+    spotlight_prepack_weights, lib, SYMBOLS,
     STAGES, OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, F32, BF16,
 )

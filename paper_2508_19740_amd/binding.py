@@ -22,7 +22,8 @@ STAGES = ("hash_keys", "hash_query", "score", "select", "attend")
 SYMBOLS = (
     "spotlight_validate_config", "spotlight_workspace_bytes", "spotlight_create", "spotlight_destroy",
     "spotlight_set_stream", "spotlight_strerror", "spotlight_hash_keys", "spotlight_retrieve_topk",
-    "spotlight_sparse_decode", "spotlight_decode_step", "spotlight_profile_enable", "spotlight_profile_read",
+    "spotlight_sparse_decode", "spotlight_decode_step", "spotlight_prepack_weights", "spotlight_profile_enable",
+    "spotlight_profile_read",
 )
 
 
@@ -59,6 +60,7 @@ def _load() -> C.CDLL:
     lib.spotlight_sparse_decode.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, vp]
     lib.spotlight_decode_step.argtypes = [vp, vp, vp, vp, C.POINTER(HashWeights), vp, i64, i32, i32, i32,
                                           C.c_float, vp, vp]
+    lib.spotlight_prepack_weights.argtypes = [vp, C.POINTER(HashWeights)]
     lib.spotlight_profile_enable.argtypes = [vp, C.c_int]
     lib.spotlight_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
     return lib
@@ -157,6 +159,17 @@ class Spotlight:
             lib.spotlight_set_stream(self._h, s)
 
     # ------------------------------------------------------------------ entry points
+    def prepack_weights(self, w1=None, b1=None, w2=None):
+        """Copy the hash weights into the kernel's read order (all None: drop the copy)."""
+        self._sync_stream()
+        if w1 is None:
+            rc = lib.spotlight_prepack_weights(self._h, None)
+        else:
+            w = self._weights(w1, b1, w2)
+            rc = lib.spotlight_prepack_weights(self._h, C.byref(w))
+        if rc != OK:
+            raise SpotlightError(rc, "spotlight_prepack_weights")
+
     def hash_keys(self, K, w1, b1, w2, t0: int, n_new: int, codes):
         self._sync_stream()
         kp = self._chk(K, (self.B, self.Hkv, self.Nmax, self.d), self.kv_dtype, "K")
@@ -259,6 +272,10 @@ def spotlight_retrieve_topk(ctx: Spotlight, q, w1, b1, w2, codes, n_tokens, k, *
 
 def spotlight_sparse_decode(ctx: Spotlight, q, K, V, idx, scale=None, out=None):
     return ctx.sparse_decode(q, K, V, idx, scale, out)
+
+
+def spotlight_prepack_weights(ctx: Spotlight, w1=None, b1=None, w2=None):
+    return ctx.prepack_weights(w1, b1, w2)
 
 
 def spotlight_decode_step(ctx: Spotlight, q, K, V, w1, b1, w2, codes, n_tokens, k, n_sink=0, n_local=0, **kw):

@@ -55,6 +55,10 @@ int make_plan(const spotlight_config* c, Plan* p)
     p->off_part_ml = off;   off = align_up(off + BH * p->max_splits * 8, 256);
     p->off_part_acc = off;  off = align_up(off + BH * p->max_splits * static_cast<size_t>(kHeadDim) * 4, 256);
     p->off_wnorm = off;     off = align_up(off + static_cast<size_t>(p->Hkv) * p->L * 4, 256);
+    pack_sizes(p->hidden, p->L, &p->pack_w1_elems, &p->pack_out_elems);
+    const size_t welem = p->w_dtype == SPOTLIGHT_BF16 ? 2 : 4;
+    p->off_pack_w1 = off;   off = align_up(off + static_cast<size_t>(p->Hkv) * p->pack_w1_elems * welem, 256);
+    p->off_pack_out = off;  off = align_up(off + static_cast<size_t>(p->Hkv) * p->pack_out_elems * welem, 256);
     p->total_bytes = off;
     return SPOTLIGHT_OK;
 }
@@ -178,6 +182,15 @@ int spotlight_set_stream(spotlight_ctx* ctx, void* stream)
     return SPOTLIGHT_OK;
 }
 
+// The packed copy of the weights serves a job only if it was made from exactly these arrays.
+static void attach_packed(const spotlight_ctx* ctx, const spotlight_hash_weights* w, HashLaunch* h)
+{
+    const Plan& p = ctx->plan;
+    const bool match = ctx->packed_w1 && ctx->packed_w1 == w->w1 && ctx->packed_b1 == w->b1 && ctx->packed_w2 == w->w2;
+    h->pack_w1 = match && p.pack_w1_elems ? ctx->workspace + p.off_pack_w1 : nullptr;
+    h->pack_out = match && p.pack_out_elems ? ctx->workspace + p.off_pack_out : nullptr;
+}
+
 // The hash job of n_new key rows of every (batch, kv head), written into the code cache.
 static HashLaunch key_job(const spotlight_ctx* ctx, const void* K, const spotlight_hash_weights* w, int64_t t0,
                           int64_t n_new, uint32_t* codes)
@@ -204,6 +217,7 @@ static HashLaunch key_job(const spotlight_ctx* ctx, const void* K, const spotlig
     h.zero = nullptr;
     h.zero_words = 0;
     h.wnorm = reinterpret_cast<float*>(ctx->workspace + p.off_wnorm);
+    attach_packed(ctx, w, &h);
     return h;
 }
 
@@ -233,7 +247,26 @@ static HashLaunch query_job(const spotlight_ctx* ctx, const void* q, const spotl
     h.zero = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_gcum);
     h.zero_words = p.L + 2;
     h.wnorm = nullptr;
+    attach_packed(ctx, w, &h);
     return h;
+}
+
+int spotlight_prepack_weights(spotlight_ctx* ctx, const spotlight_hash_weights* w)
+{
+    if (!ctx) return SPOTLIGHT_ERR_INVALID_ARG;
+    ctx->packed_w1 = ctx->packed_b1 = ctx->packed_w2 = nullptr;
+    if (!w) return SPOTLIGHT_OK;   // the copy is dropped
+    const Plan& p = ctx->plan;
+    const int rc = check_weights(ctx, w);
+    if (rc != SPOTLIGHT_OK) return rc;
+    if (p.pack_out_elems == 0) return SPOTLIGHT_OK;   // no kernel would read a copy for this hash shape
+    const int rc2 = launch_pack_weights(ctx, w->w1, w->w2, p.w_dtype, ctx->workspace + p.off_pack_w1,
+                                        ctx->workspace + p.off_pack_out);
+    if (rc2 != SPOTLIGHT_OK) return rc2;
+    ctx->packed_w1 = w->w1;
+    ctx->packed_b1 = w->b1;
+    ctx->packed_w2 = w->w2;
+    return SPOTLIGHT_OK;
 }
 
 int spotlight_hash_keys(spotlight_ctx* ctx, const void* K, const spotlight_hash_weights* w, int64_t t0,

@@ -33,6 +33,9 @@ struct Plan {
     size_t off_part_ml;    // [B*Hq][max_splits] {max, sum} of each attention split
     size_t off_part_acc;   // [B*Hq][max_splits][128] weighted value sums of each split
     size_t off_wnorm;      // [Hkv][L] norms of the second hash layer's rows (bulk hashing on the matrix cores)
+    size_t off_pack_w1;    // first hash layer in the single-vector kernel's read order (pack_w1_elems per kv head)
+    size_t off_pack_out;   // output matrix of the hash (W2, or R of the linear hash) in that order
+    size_t pack_w1_elems, pack_out_elems;   // elements per kv head; both 0 if the hash shape has no such copy
     size_t total_bytes;
 };
 
@@ -77,6 +80,10 @@ struct spotlight_ctx {
     char* workspace;
     int max_lds;                     // bytes of LDS one workgroup may use on this device
     int n_cus;                       // compute units of this device
+    // the weights the packed copy in the workspace was made from (all null: no copy)
+    const void* packed_w1;
+    const void* packed_b1;
+    const void* packed_w2;
     // profiling
     int profiling;
     int n_rec;                       // records in use since the last read
@@ -116,8 +123,14 @@ struct HashLaunch {
     uint32_t* zero;           // if set: zero[xhead * zero_words ...) is cleared by the head's first tile
     int zero_words;
     float* wnorm;             // [weight heads][L] floats of scratch for the matrix-core path, or null
+    const void* pack_w1;      // packed copies of the weights (see launch_pack_weights), or null
+    const void* pack_out;
 };
 int launch_hash(spotlight_ctx* ctx, const HashLaunch& a, int stage);
+// Elements per weight head of the packed copies the single-vector hash kernel can read (0: none).
+void pack_sizes(int hidden, int L, size_t* w1_elems, size_t* out_elems);
+// Writes the packed copies of w1 and of the output matrix (w2, or w1 itself for the linear hash).
+int launch_pack_weights(spotlight_ctx* ctx, const void* w1, const void* w2, int w_dtype, void* pack_w1, void* pack_out);
 // Two hash jobs; one launch when both hash a single vector per head with the same network shape.
 int launch_hash_pair(spotlight_ctx* ctx, const HashLaunch& a, const HashLaunch& b, int stage);
 

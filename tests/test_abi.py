@@ -82,6 +82,10 @@ def test_workspace_grows_with_the_problem():
     assert big > small
     # about one byte per (query head, token) for the candidate lists, plus histograms
     assert big < 32 * (1 << 20) * 2
+    # room for one packed copy of the hash weights: about their own size
+    wide = sp.workspace_bytes(_cfg(max_tokens=4096, hidden=1024, code_bits=512))
+    more_weights = 32 * ((1024 * 128 + 512 * 1024) - (256 * 128 + 128 * 256)) * 2   # bf16, 32 kv heads
+    assert more_weights <= wide - small <= more_weights + (1 << 20)
 
 
 def test_null_arguments_are_rejected_without_a_gpu():
@@ -92,6 +96,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.spotlight_hash_keys(None, None, None, 0, 0, None) == bad
     assert lib.spotlight_retrieve_topk(None, None, None, None, 1, 1, None, None, None) == bad
     assert lib.spotlight_sparse_decode(None, None, None, None, None, 1, 0.1, None) == bad
+    assert lib.spotlight_prepack_weights(None, None) == bad
     assert lib.spotlight_profile_enable(None, 1) == bad
     assert lib.spotlight_profile_read(None, 0, None, None) == bad
     assert lib.spotlight_set_stream(None, None) == bad

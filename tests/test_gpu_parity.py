@@ -30,6 +30,14 @@ SMALL = {
     "one_word": C["C1"].scaled(n_tokens=1300, topk=200, code_bits=32, hidden=8, needles=2),
     "f32_kv_bf16_w": C["C1"].scaled(n_tokens=777, topk=77, weight_dtype="bf16", needles=2),
     "g8": C["C4"].scaled(batch=1, n_q_heads=8, n_kv_heads=1, n_tokens=4200, topk=100, code_bits=128, hidden=256, needles=1),
+    # more query + key vectors per step than compute units: the hash kernel that serves several
+    # vectors of one weight head per workgroup (full tiles; ragged last tiles; the linear hash)
+    "many_vectors": C["C4"].scaled(batch=20, n_q_heads=16, n_kv_heads=4, n_tokens=700 + 3, topk=90, hidden=128,
+                                   code_bits=128, needles=1),
+    "many_vectors_ragged": C["C4"].scaled(batch=7, n_q_heads=40, n_kv_heads=20, n_tokens=500 + 9, topk=80, hidden=128,
+                                          code_bits=64, needles=1),
+    "many_vectors_lin": C["C4"].scaled(batch=9, n_q_heads=32, n_kv_heads=16, n_tokens=400 + 1, topk=75, hidden=0,
+                                       code_bits=128, needles=1),
 }
 
 

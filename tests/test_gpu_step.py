@@ -23,6 +23,14 @@ SMALL = {
                                    lsh_init="rotation", needles=2),
     "block_edge": C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=3 * 4096, topk=200, needles=2),
     "g8": C["C4"].scaled(batch=1, n_q_heads=8, n_kv_heads=1, n_tokens=4200, topk=100, code_bits=128, hidden=256, needles=1),
+    # more query + key vectors per step than compute units: the hash kernel that serves several
+    # vectors of one weight head per workgroup (full tiles; ragged last tiles; the linear hash)
+    "many_vectors": C["C4"].scaled(batch=20, n_q_heads=16, n_kv_heads=4, n_tokens=700 + 3, topk=90, hidden=128,
+                                   code_bits=128, needles=1),
+    "many_vectors_ragged": C["C4"].scaled(batch=7, n_q_heads=40, n_kv_heads=20, n_tokens=500 + 9, topk=80, hidden=128,
+                                          code_bits=64, needles=1),
+    "many_vectors_lin": C["C4"].scaled(batch=9, n_q_heads=32, n_kv_heads=16, n_tokens=400 + 1, topk=75, hidden=0,
+                                       code_bits=128, needles=1),
 }
 FORCED = [(0, 0), (4, 64), (0, 1), (7, 0)]
 
@@ -82,6 +90,76 @@ def test_step_without_forced_tokens_equals_the_three_calls(case):
     assert torch.equal(case.codes, c2)
     assert torch.equal(idx, idx2)
     assert torch.equal(out, out2)
+
+
+def test_prepacked_weights_change_nothing_but_the_load_order(case):
+    """With the packed copy of the weights in the workspace, the decode step, the retrieval alone
+    and the one-key append give the oracle's codes and indices, and the same attention output."""
+    cfg = case.cfg
+    n = cfg.n_tokens
+    want_codes = case.base_codes.clone()
+    want_idx, want_out = oracle.decode_step(case.w.q, case.hK, case.hV, *case.hweights, want_codes, n, cfg.topk,
+                                            4, 64, case.scale)
+    case.codes.copy_(case.base_codes)
+    _, out_plain = case.ctx.decode_step(case.q, case.K, case.V, *case.weights, case.codes, n, cfg.topk, 4, 64)
+    case.ctx.prepack_weights(*case.weights)
+    try:
+        case.codes.copy_(case.base_codes)
+        idx, out = case.ctx.decode_step(case.q, case.K, case.V, *case.weights, case.codes, n, cfg.topk, 4, 64)
+        assert torch.equal(case.codes.cpu(), want_codes)
+        assert torch.equal(idx.cpu(), want_idx)
+        assert float((out.cpu() - want_out).abs().max()) <= ATTN_TOL
+        assert torch.equal(out, out_plain)
+        # the single calls read the copy as well
+        qcode = torch.empty(cfg.batch, cfg.n_q_heads, cfg.words, dtype=torch.int32, device=case.dev)
+        idx2 = case.ctx.retrieve_topk(case.q, *case.weights, case.codes, n, cfg.topk, out_qcode=qcode)
+        widx, wq, _ = oracle.retrieve_topk(case.w.q, *case.hweights, want_codes, n, cfg.topk)
+        assert torch.equal(qcode.cpu(), wq)
+        assert torch.equal(idx2.cpu(), widx)
+        case.codes.copy_(case.base_codes)
+        case.ctx.hash_keys(case.K, *case.weights, n - 1, 1, case.codes)
+        assert torch.equal(case.codes.cpu(), want_codes)
+    finally:
+        case.ctx.prepack_weights()   # dropped: the other tests read the arrays themselves
+
+
+def test_prepacked_copy_serves_only_the_arrays_it_was_made_from():
+    """The copy is a snapshot keyed by the three pointers: other arrays are read directly, and
+    after a change in place the copy has to be made again."""
+    cfg = C["C2"].scaled(n_q_heads=4, n_kv_heads=2, n_tokens=300, topk=20, needles=1)
+    c = Case(cfg)
+    try:
+        t0 = cfg.n_tokens - 1
+
+        def oracle_row(hweights):
+            want = torch.zeros(cfg.batch, cfg.n_kv_heads, cfg.max_tokens, cfg.words, dtype=torch.int32)
+            oracle.hash_keys(c.hK, *hweights, cfg.code_bits, t0, 1, want)
+            return want
+
+        w1, b1, w2 = c.weights
+        hw1, hb1, hw2 = c.hweights
+        c.ctx.prepack_weights(w1, b1, w2)
+        # other arrays (every output's sign flipped): their own contents count, not the copy
+        w2_neg = (-w2).contiguous()
+        c.codes.zero_()
+        c.ctx.hash_keys(c.K, w1, b1, w2_neg, t0, 1, c.codes)
+        want_neg = oracle_row((hw1, hb1, -hw2))
+        assert torch.equal(c.codes.cpu(), want_neg)
+        assert not torch.equal(want_neg, oracle_row((hw1, hb1, hw2)))
+        # changed in place and packed again
+        w2.neg_()
+        c.ctx.prepack_weights(w1, b1, w2)
+        c.codes.zero_()
+        c.ctx.hash_keys(c.K, w1, b1, w2, t0, 1, c.codes)
+        assert torch.equal(c.codes.cpu(), want_neg)
+        # dropped: back to the arrays
+        c.ctx.prepack_weights()
+        w2.neg_()
+        c.codes.zero_()
+        c.ctx.hash_keys(c.K, w1, b1, w2, t0, 1, c.codes)
+        assert torch.equal(c.codes.cpu(), oracle_row((hw1, hb1, hw2)))
+    finally:
+        c.close()
 
 
 def test_decode_step_rejects_bad_arguments(case):
