@@ -464,6 +464,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
         lt_bits[i * THREADS + tid] = 0;
         eq_bits[i * THREADS + tid] = 0;
     }
+#pragma unroll 4
     for (int bin = tid; bin < BINS; bin += THREADS) {
         const uint32_t c = gc[bin];
         const uint32_t p = bin ? gc[bin - 1] : 0u;
@@ -477,8 +478,12 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
     __syncthreads();
     const uint32_t T = s_T, r = s_r;
 
+    // this block's own counts are requested together with those of the blocks before it
+    const uint32_t own_le = bc[static_cast<int64_t>(blk) * BINS + T];
+    const uint32_t own_lt = T ? bc[static_cast<int64_t>(blk) * BINS + T - 1] : 0u;
     // tokens below T and in the tie bucket, in the blocks before this one
     uint32_t lt = 0, eq = 0;
+#pragma unroll 4
     for (int j = tid; j < blk; j += THREADS) {
         const uint32_t le = bc[static_cast<int64_t>(j) * BINS + T];
         const uint32_t l = T ? bc[static_cast<int64_t>(j) * BINS + T - 1] : 0u;
@@ -493,8 +498,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
         lt = red[0][0] + red[0][1];
         eq = red[1][0] + red[1][1];
     }
-    const uint32_t own_le = bc[static_cast<int64_t>(blk) * BINS + T];
-    const uint32_t own_lt = T ? bc[static_cast<int64_t>(blk) * BINS + T - 1] : 0u;
     const uint32_t own_eq = own_le - own_lt;
     // Ties go to earlier blocks first.  Written without any subtraction that could wrap.
     const uint32_t taken_before = eq < r ? eq : r;              // ties taken by the blocks before
