@@ -109,8 +109,9 @@ const char *spotlight_strerror(int rc);
  * key: 28 -> 15 us for 640 vectors of a 128 -> 512 -> 256 network).  Later calls that pass the same
  * three pointers use the copy; the codes are the same bit for bit.  The copy is made on the
  * context's stream, in stream order with the calls around it.  It is a snapshot: after changing the
- * CONTENTS of the arrays call this again (or pass NULL to drop the copy); calls that pass other
- * pointers read their own arrays.  Hidden widths that are not a multiple of 128 have no such
+ * CONTENTS of the arrays (an update in place, or memory freed and handed out again at the same
+ * address) call this again, or pass NULL to drop the copy; calls that pass other pointers read
+ * their own arrays.  Hidden widths that are not a multiple of 128 have no such
  * kernel: the call succeeds and changes nothing.
  * Errors: INVALID_ARG for a NULL context or missing / misaligned arrays.
  */

@@ -187,6 +187,7 @@ def test_c3_512k_tokens():
         idx = check_sampled_heads_real_chain(big, [(0, 5), (0, 31)])
         check_attention_all_heads(big, idx)
         check_retrieval_on_synthetic_codes(big)
+        big.ctx.prepack_weights(*big.weights)      # as bench.py runs the step
         check_decode_step_on_synthetic_codes(big)
     finally:
         big.close()
@@ -198,6 +199,7 @@ def test_c4_gqa_batch16():
         idx = check_sampled_heads_real_chain(big, [(0, 0), (9, 3), (15, 7)])
         check_attention_all_heads(big, idx)
         check_retrieval_on_synthetic_codes(big)
+        big.ctx.prepack_weights(*big.weights)      # as bench.py runs the step
         check_decode_step_on_synthetic_codes(big, attn_every=7)
     finally:
         big.close()
@@ -219,6 +221,7 @@ def test_c5_one_million_tokens_with_growth(c5_kv, name):
         N = c.n_tokens
         # bulk build, then three decode-step appends
         big.ctx.hash_keys(big.K, *big.weights, 0, N, big.codes)
+        big.ctx.prepack_weights(*big.weights)      # the appends and the query hash read the packed copy, as in bench.py
         for j in range(3):
             big.ctx.hash_keys(big.K, *big.weights, N + j, 1, big.codes)
         # sampled rows of sampled heads, including both ends, a tile boundary and the appended keys
