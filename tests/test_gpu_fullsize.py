@@ -91,17 +91,18 @@ def check_retrieval_on_synthetic_codes(big, n_tokens=None):
     return idx
 
 
-def check_decode_step_on_synthetic_codes(big, n_sink=4, n_local=64, attn_every=1):
+def check_decode_step_on_synthetic_codes(big, n_sink=4, n_local=64, attn_every=1, k=None):
     """Every head: the one-call step (appended key hashed into generated codes, forced sink / local
     tokens, attention) against the oracle's single steps on the same codes (attention on every
     attn_every-th head)."""
     c = big.cfg
     n = c.n_tokens
     G = c.group
+    k = c.topk if k is None else k
     dcodes = big.synthetic_codes()
-    idx, out = big.ctx.decode_step(big.q, big.K, big.V, *big.weights, dcodes, n, c.topk, n_sink, n_local)
+    idx, out = big.ctx.decode_step(big.q, big.K, big.V, *big.weights, dcodes, n, k, n_sink, n_local)
     idx, out = idx.cpu(), out.cpu()
-    ar = torch.arange(c.topk, dtype=torch.int32)
+    ar = torch.arange(k, dtype=torch.int32)
     worst = 0.0
     for b in range(c.batch):
         for hk in range(c.n_kv_heads):
@@ -115,7 +116,7 @@ def check_decode_step_on_synthetic_codes(big, n_sink=4, n_local=64, attn_every=1
                 hq = hk * G + g
                 _, qc = oracle.hash_rows(big.w.q[b, hq:hq + 1].contiguous(), *big.head_weights(hk), c.code_bits)
                 dist = oracle.hamming(qc[0].contiguous(), hc)
-                want = oracle.topk_forced(dist, c.topk, n_sink, n_local)
+                want = oracle.topk_forced(dist, k, n_sink, n_local)
                 assert torch.equal(idx[b, hq], want), (b, hq)
                 if (b * c.n_q_heads + hq) % attn_every:
                     continue
@@ -201,6 +202,23 @@ def test_c4_gqa_batch16():
         check_retrieval_on_synthetic_codes(big)
         big.ctx.prepack_weights(*big.weights)      # as bench.py runs the step
         check_decode_step_on_synthetic_codes(big, attn_every=7)
+    finally:
+        big.close()
+
+
+@pytest.mark.parametrize("words", [2, 5])
+def test_many_blocks_of_many_heads(words):
+    """512 query heads x 9 token blocks: more (head, block) pairs than the chip holds at once, which
+    is where retrieval switches to its single-wavefront select kernel; with and without forced
+    tokens, for code lengths other than those of C4 and C5."""
+    cfg = wl.CONFIGS["C4"].scaled(batch=8, n_q_heads=64, n_kv_heads=8, n_tokens=8 * 4096 + 77, topk=9400,
+                                  hidden=128, code_bits=32 * words, needles=0, seed=4242 + words)
+    big = Big(cfg)
+    try:
+        check_decode_step_on_synthetic_codes(big, n_sink=0, n_local=0, attn_every=61, k=300)
+        check_decode_step_on_synthetic_codes(big, n_sink=4, n_local=64, attn_every=67, k=300)
+        big.ctx.prepack_weights(*big.weights)
+        check_decode_step_on_synthetic_codes(big, n_sink=5000, n_local=4100, attn_every=509, k=9400)   # windows wider than a block
     finally:
         big.close()
 
