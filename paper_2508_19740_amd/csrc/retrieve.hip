@@ -7,16 +7,19 @@
 //           codes of its block, XORs them with the G query codes of the group and popcounts; the
 //           16 distances of each thread stay in registers.  The block counts them in an LDS
 //           histogram (replicated over lanes so that same-address atomics stay apart), turns it
-//           into a cumulative histogram, stores that per block and adds it to the cumulative
+//           into a cumulative histogram and adds it to a running one that covers the blocks of
+//           the head the workgroup has counted so far (its "run" of consecutive blocks).  The
+//           running histogram is stored per block, and once per run added to the cumulative
 //           histogram of the head (integer atomics).  It then keeps a short list of CANDIDATES:
 //           the tokens up to a block-local distance bound chosen so that about twice the block's
 //           fair share of k qualifies (one sub-list per wavefront).  Nothing else is written per
 //           token.  Workgroups are persistent and fetch the next keys before finishing a block.
 //   select  one workgroup per (query head, block).  The head's cumulative histogram gives the
 //           exact threshold T with count(d < T) < k <= count(d <= T) and r = k - count(d < T),
-//           the number of tokens to take from the tie bucket d == T.  The cumulative histograms of
-//           the preceding blocks give this block's output offset and its share of the tie bucket
-//           (ties go to the lower token index).  If T is within the block's candidate bound, the
+//           the number of tokens to take from the tie bucket d == T.  The stored histograms of
+//           the block in front (same run) and of the last block of every run before give this
+//           block's own counts, its output offset and its share of the tie bucket (ties go to
+//           the lower token index).  If T is within the block's candidate bound, the
 //           block's tokens with d <= T are all in its list; otherwise (rare) the block recomputes
 //           its distances from the codes.  Selected tokens are marked in an LDS bitmap and written
 //           out in increasing token order.
@@ -45,9 +48,12 @@ constexpr int kKPT = kTPB / kThreads;       // keys per thread (16)
 constexpr int kWaveCap = kCandCap / (kThreads / 64);  // entries of one wavefront's candidate sub-list (256)
 constexpr int kWaveFull = 255;              // count value meaning "this sub-list overflowed"
 
-// Per (query head, token block): the block's candidate bound and its four sub-list lengths.
+// Per (query head, token block): the block's candidate bound (a bin, low kBoundBits bits), the
+// first block of the run of blocks its workgroup counted together (the bits above), and the four
+// sub-list lengths.
+constexpr int kBoundBits = 11;   // bins go up to 32 * 32 + 1
 struct BlockMeta {
-    uint32_t bound;
+    uint32_t bound_run;
     uint8_t count[kThreads / 64];
 };
 static_assert(sizeof(BlockMeta) == 8, "workspace layout");
@@ -166,12 +172,14 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
     };
     if (AHEAD && task0 < task1) fetch(std::false_type{}, task0, 0, buf[0]);
 
+    int run_begin = 0;   // first block of the current run: consecutive blocks of one head counted by this workgroup
     for (int task = task0; task < task1; ++task) {
         const int bk = task / a.nblk, blk = task % a.nblk;
         const int b = bk / a.Hkv, hk = bk % a.Hkv;
         const int64_t bh0 = static_cast<int64_t>(b) * Hq + hk * G;  // first query head of the group
         const int64_t t_begin = static_cast<int64_t>(blk) * kTPB;
         const int n_blk = static_cast<int>(min(static_cast<int64_t>(kTPB), a.n_tokens - t_begin));
+        if (task == task0 || blk == 0) run_begin = blk;   // gacc starts from zero here
         // this lane's part of the G query codes (the whole code when a lane owns whole keys)
         uint32_t qc[G][CWL];
 #pragma unroll
@@ -323,14 +331,16 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
         }
         __syncthreads();
 
-        // publish: the block's cumulative histogram (contiguous store), and, at the end of a run of
-        // tasks of one head group, the accumulated histogram into the head's global one
+        // publish: the cumulative histogram of the run up to and including this block (contiguous
+        // store; select takes differences of neighbouring blocks and sums over the runs in front,
+        // instead of summing over every block in front), and, at the end of a run, the same
+        // numbers into the head's global histogram
         const bool flush = task + 1 == task1 || (task + 1) / a.nblk != bk;
         for (int i = tid; i < G * BINS; i += kThreads) {
             const int g = i / BINS, bin = i % BINS;
-            a.blockcum[((bh0 + g) * a.max_blocks + blk) * BINS + bin] = cum[i];
+            const uint32_t v = gacc[i];
+            a.blockcum[((bh0 + g) * a.max_blocks + blk) * BINS + bin] = v;
             if (flush) {
-                const uint32_t v = gacc[i];
                 if (v) atomicAdd(&a.gcum[(bh0 + g) * BINS + bin], v);
                 gacc[i] = 0;
             }
@@ -379,7 +389,7 @@ __global__ __launch_bounds__(kThreads, score_min_waves(W, G)) void score_kernel(
             if (lane == 0) {
                 BlockMeta* bm = a.blockmeta + slot;
                 bm->count[wave] = total < static_cast<uint32_t>(kWaveFull) ? static_cast<uint8_t>(total) : static_cast<uint8_t>(kWaveFull);
-                if (wave == 0) bm->bound = thi;
+                if (wave == 0) bm->bound_run = thi | (static_cast<uint32_t>(run_begin) << kBoundBits);
             }
         }
         // the next task's first barrier orders these reads of cum / s_thi / gacc before their reuse
@@ -416,7 +426,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
     const uint32_t* __restrict__ codes, const uint32_t* __restrict__ qcode, const uint32_t* __restrict__ gcum,
     const uint32_t* __restrict__ blockcum, const BlockMeta* __restrict__ blockmeta, const uint32_t* __restrict__ cand,
     int32_t* __restrict__ out_idx, int64_t n_tokens, int64_t Nmax, int Hq, int Hkv, int max_blocks, int k,
-    int64_t n_sink, int64_t local_begin)
+    int64_t n_sink, int64_t local_begin, int tasks_per_group)
 {
     constexpr int BINS = W * 32 + 2;   // bin 0: forced tokens; bin d + 1: distance d
     constexpr int NW = THREADS / 64;
@@ -431,7 +441,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
     constexpr uint32_t kDenseOutput = 512;
     constexpr uint32_t kDenseChunk = 1024;
     __shared__ uint32_t s_T, s_r;
-    __shared__ uint32_t red[2][NW];
+    __shared__ uint32_t red[3][2];
     __shared__ uint32_t lt_bits[WORDS], eq_bits[WORDS];
     __shared__ uint32_t wsum[NW];
     __shared__ uint16_t dense[kDenseChunk];   // offsets of selected tokens, for blocks selected almost whole
@@ -478,26 +488,48 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
     __syncthreads();
     const uint32_t T = s_T, r = s_r;
 
-    // this block's own counts are requested together with those of the blocks before it
-    const uint32_t own_le = bc[static_cast<int64_t>(blk) * BINS + T];
-    const uint32_t own_lt = T ? bc[static_cast<int64_t>(blk) * BINS + T - 1] : 0u;
-    // tokens below T and in the tie bucket, in the blocks before this one
+    // The rows of `bc` are cumulative over the blocks of a run (the consecutive blocks of the head
+    // that one score workgroup counted).  This block's own counts are its row minus the row in
+    // front (within the run); the tokens below T and in the tie bucket in all blocks before this
+    // one are that row in front plus the last rows of the runs before this one.  Every run between
+    // the head's first and this one is tasks_per_group blocks long, so those last rows are
+    // tasks_per_group apart.  All requested together.
+    const int rb = min(static_cast<int>(meta.bound_run >> kBoundBits), blk);   // first block of this block's run
+    const uint32_t cur_le = bc[static_cast<int64_t>(blk) * BINS + T];
+    const uint32_t cur_lt = T ? bc[static_cast<int64_t>(blk) * BINS + T - 1] : 0u;
+    // thread 0 takes the row in front, thread m >= 1 the last row of the m-th run before this one
     uint32_t lt = 0, eq = 0;
-#pragma unroll 4
-    for (int j = tid; j < blk; j += THREADS) {
+    const int step = min(tasks_per_group, blk + 1);   // a longer step leaves the head at once anyway
+    int j = tid == 0 ? (blk > rb ? blk - 1 : -1) : rb - 1 - (tid - 1) * step;
+    uint32_t first_le = 0, first_lt = 0;   // what thread 0 read
+    if (j >= 0) {
+        first_le = bc[static_cast<int64_t>(j) * BINS + T];
+        first_lt = T ? bc[static_cast<int64_t>(j) * BINS + T - 1] : 0u;
+        lt = first_lt;
+        eq = first_le - first_lt;
+    }
+    // more than THREADS - 1 runs in front: the THREADS - 1 threads that walk them go round again
+    for (j = tid == 0 ? -1 : j - (THREADS - 1) * step; j >= 0; j -= (THREADS - 1) * step) {
         const uint32_t le = bc[static_cast<int64_t>(j) * BINS + T];
         const uint32_t l = T ? bc[static_cast<int64_t>(j) * BINS + T - 1] : 0u;
         lt += l;
         eq += le - l;
     }
+    uint32_t prev_le = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(first_le)));
+    uint32_t prev_lt = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(first_lt)));
     lt = wave_sum(lt);
     eq = wave_sum(eq);
     if constexpr (NW > 1) {
         if (lane == 0) { red[0][wave] = lt; red[1][wave] = eq; }
+        if (tid == 0) { red[2][0] = first_le; red[2][1] = first_lt; }
         __syncthreads();
         lt = red[0][0] + red[0][1];
         eq = red[1][0] + red[1][1];
+        prev_le = red[2][0];
+        prev_lt = red[2][1];
     }
+    const uint32_t own_le = cur_le - prev_le;
+    const uint32_t own_lt = cur_lt - prev_lt;
     const uint32_t own_eq = own_le - own_lt;
     // Ties go to earlier blocks first.  Written without any subtraction that could wrap.
     const uint32_t taken_before = eq < r ? eq : r;              // ties taken by the blocks before
@@ -513,7 +545,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
         static_cast<uint32_t>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), n_sink - t_begin)));
     const uint32_t local_off = !FORCED ? static_cast<uint32_t>(n_blk) :
         static_cast<uint32_t>(max(static_cast<int64_t>(0), min(static_cast<int64_t>(n_blk), local_begin - t_begin)));
-    bool listed = T <= meta.bound;
+    bool listed = T <= (meta.bound_run & ((1u << kBoundBits) - 1));
 #pragma unroll
     for (int s = 0; s < SUB; ++s) listed = listed && meta.count[s] != kWaveFull;
     if (listed) {
@@ -669,7 +701,7 @@ struct RetrieveArgs {
 };
 
 template <int W, int G>
-int launch_score_wg(spotlight_ctx* ctx, const RetrieveArgs& a)
+int launch_score_wg(spotlight_ctx* ctx, const RetrieveArgs& a, int* tasks_per_group)
 {
     const Plan& p = ctx->plan;
     constexpr int BINS = W * 32 + 2;
@@ -708,6 +740,7 @@ int launch_score_wg(spotlight_ctx* ctx, const RetrieveArgs& a)
     s.k = a.k;
     s.total_tasks = a.nblk * p.B * p.Hkv;
     s.tasks_per_group = (s.total_tasks + resident - 1) / resident;
+    *tasks_per_group = s.tasks_per_group;
     const int grid = (s.total_tasks + s.tasks_per_group - 1) / s.tasks_per_group;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), 0, ctx->stream, s);
     return SPOTLIGHT_OK;
@@ -719,18 +752,19 @@ int launch_w(spotlight_ctx* ctx, const RetrieveArgs& a)
     const Plan& p = ctx->plan;
     const int BH = p.B * p.Hq;
     const uint32_t* qcode = reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_qcode);
+    int tasks_per_group = 1;
     {
         StageTimer timer(ctx, SPOTLIGHT_STAGE_SCORE);
         int rc;
         switch (p.G) {
-        case 1: rc = launch_score_wg<W, 1>(ctx, a); break;
-        case 2: rc = launch_score_wg<W, 2>(ctx, a); break;
+        case 1: rc = launch_score_wg<W, 1>(ctx, a, &tasks_per_group); break;
+        case 2: rc = launch_score_wg<W, 2>(ctx, a, &tasks_per_group); break;
         case 4:
             // 1024-bit codes: the histograms of more than two heads do not fit in LDS
-            if constexpr (W <= 16) { rc = launch_score_wg<W, 4>(ctx, a); break; }
+            if constexpr (W <= 16) { rc = launch_score_wg<W, 4>(ctx, a, &tasks_per_group); break; }
             return SPOTLIGHT_ERR_UNSUPPORTED;
         case 8:
-            if constexpr (W <= 16) { rc = launch_score_wg<W, 8>(ctx, a); break; }
+            if constexpr (W <= 16) { rc = launch_score_wg<W, 8>(ctx, a, &tasks_per_group); break; }
             return SPOTLIGHT_ERR_UNSUPPORTED;
         default: return SPOTLIGHT_ERR_UNSUPPORTED;
         }
@@ -752,7 +786,7 @@ int launch_w(spotlight_ctx* ctx, const RetrieveArgs& a)
                            reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_blockcum),
                            reinterpret_cast<const BlockMeta*>(ctx->workspace + p.off_blockmeta),
                            reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_cand), a.out_idx, a.n_tokens,
-                           p.Nmax, p.Hq, p.Hkv, p.max_blocks, a.k, a.n_sink, a.local_begin);
+                           p.Nmax, p.Hq, p.Hkv, p.max_blocks, a.k, a.n_sink, a.local_begin, tasks_per_group);
         if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
     }
     if (a.out_dist) {

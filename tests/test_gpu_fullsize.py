@@ -223,6 +223,27 @@ def test_many_blocks_of_many_heads(words):
         big.close()
 
 
+@pytest.mark.parametrize("shape", [(1, 32, 32, 40 * 4096 + 100, 4), (2, 32, 16, 69 * 4096 + 4000, 3), (1, 8, 1, 700 * 4096 + 9, 8),
+                                   (1, 4, 4, 599 * 4096 + 77, 4), (1, 8, 8, 601 * 4096 + 5, 2)])
+def test_runs_of_blocks_that_straddle_heads(shape):
+    """More (kv head, block) tasks than resident score workgroups, so that a workgroup counts a run
+    of two or three consecutive blocks, with block counts that are no multiple of the run length
+    (runs then start in one head and end in the next); one head of 701 blocks on its own; and heads
+    with more runs than a select workgroup has threads (200 runs of 3 blocks with 128 threads, 121
+    runs of 5 with 64).  The select kernel rebuilds every block's counts and offsets from the runs'
+    cumulative histograms."""
+    batch, hq, hkv, n, words = shape
+    k = max(2000, n // 300)
+    cfg = wl.CONFIGS["C3"].scaled(batch=batch, n_q_heads=hq, n_kv_heads=hkv, n_tokens=n, topk=k + 4300,
+                                  hidden=128, code_bits=32 * words, needles=0, seed=777 + hq + words)
+    big = Big(cfg)
+    try:
+        check_decode_step_on_synthetic_codes(big, n_sink=0, n_local=0, attn_every=13, k=k)
+        check_decode_step_on_synthetic_codes(big, n_sink=4, n_local=4200, attn_every=17, k=k + 4300)
+    finally:
+        big.close()
+
+
 @pytest.fixture(scope="module")
 def c5_kv():
     """K and V of config C5 (the 128-bit and 512-bit variants share them): 2 x 34 GB on the device."""
