@@ -47,6 +47,8 @@ constexpr int kKPT = kTPB / kThreads;       // keys per thread (16)
 
 constexpr int kWaveCap = kCandCap / (kThreads / 64);  // entries of one wavefront's candidate sub-list (256)
 constexpr int kWaveFull = 255;              // count value meaning "this sub-list overflowed"
+constexpr int kLongRun = 16;                // blocks per resident workgroup from which runs are cut short
+constexpr int kShortRun = 4;
 
 // Per (query head, token block): the block's candidate bound (a bin, low kBoundBits bits), the
 // first block of the run of blocks its workgroup counted together (the bits above), and the four
@@ -740,6 +742,13 @@ int launch_score_wg(spotlight_ctx* ctx, const RetrieveArgs& a, int* tasks_per_gr
     s.k = a.k;
     s.total_tasks = a.nblk * p.B * p.Hkv;
     s.tasks_per_group = (s.total_tasks + resident - 1) / resident;
+    // Long streams (gigabytes of codes): short runs, handed out by the hardware as workgroups
+    // retire, instead of one long run per resident workgroup.  The workgroups in flight then read
+    // one window of memory that moves through the cache in order, and uneven progress evens out
+    // (1M tokens x 128 heads, 512-bit codes: 1474 us with runs of 32 blocks, 1438 us with runs of
+    // 4, 1413 us with single blocks, which cost the shorter streams their look-ahead: 49 against
+    // 46.5 us for 512K tokens x 32 heads).  Two generations of workgroups are the worst case.
+    if (s.tasks_per_group >= kLongRun) s.tasks_per_group = kShortRun;
     *tasks_per_group = s.tasks_per_group;
     const int grid = (s.total_tasks + s.tasks_per_group - 1) / s.tasks_per_group;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), 0, ctx->stream, s);
