@@ -42,7 +42,7 @@ def parse():
     ap.add_argument("--no-prepack", action="store_true",
                     help="hash from the weight arrays as stored (no packed copy in the contexts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-heads", type=int, default=2, help="heads in the oracle's timed sample")
+    ap.add_argument("--cpu-heads", type=int, default=6, help="heads in the oracle's timed sample")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 10 plain device copies of 1 GiB (a kernel of known HBM traffic, for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
