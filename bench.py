@@ -278,7 +278,8 @@ def main():
         "timing": "HIP events around each launch, second pass over the same steps",
     }
     roofline_attend = {
-        "kernel": "attend_kernel + merge_kernel (gather, split-k softmax attention, merge of the partials)",
+        "kernel": "attend_kernel (gather + split-k softmax attention; the merge of the partials is a kernel of its "
+                  "own, kernel_us.merge)",
         "bound": "hbm",
         "achieved": round(gbps(attend_bytes, stage_us["attend"]), 1),
         "peak": HBM_PEAK_GBPS,

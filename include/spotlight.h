@@ -52,8 +52,9 @@ enum {
     SPOTLIGHT_STAGE_HASH_QUERY = 1, /* hash + pack of the query vectors                          */
     SPOTLIGHT_STAGE_SCORE = 2,      /* Hamming distances, histograms, candidate lists            */
     SPOTLIGHT_STAGE_SELECT = 3,     /* threshold, offsets, ordered output of the selected tokens */
-    SPOTLIGHT_STAGE_ATTEND = 4,     /* gather + softmax attention (partials and their merge)     */
-    SPOTLIGHT_STAGE_COUNT = 5
+    SPOTLIGHT_STAGE_ATTEND = 4,     /* gather + softmax attention over a split of the rows       */
+    SPOTLIGHT_STAGE_MERGE = 5,      /* merge of the splits' partial results                      */
+    SPOTLIGHT_STAGE_COUNT = 6
 };
 
 typedef struct {

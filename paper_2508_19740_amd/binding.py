@@ -16,7 +16,7 @@ from . import build as _build
 
 F32, BF16 = 0, 1
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
-STAGES = ("hash_keys", "hash_query", "score", "select", "attend")
+STAGES = ("hash_keys", "hash_query", "score", "select", "attend", "merge")
 
 # every symbol include/spotlight.h declares
 SYMBOLS = (

@@ -267,11 +267,14 @@ int launch_t(spotlight_ctx* ctx, const void* q, const void* K, const void* V, co
     int RB = 128;
     while (RB > kAttendMinRows && heads * ((k + RB - 1) / RB) < 1024) RB >>= 1;
     const int nsplit = (k + RB - 1) / RB;
-    StageTimer timer(ctx, SPOTLIGHT_STAGE_ATTEND);  // both kernels count as the attend stage
-    if (RB == 128) launch_rb<T, 128>(ctx, q, K, V, idx, k, scale, nsplit);
-    else if (RB == 64) launch_rb<T, 64>(ctx, q, K, V, idx, k, scale, nsplit);
-    else launch_rb<T, 32>(ctx, q, K, V, idx, k, scale, nsplit);
-    if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
+    {
+        StageTimer timer(ctx, SPOTLIGHT_STAGE_ATTEND);
+        if (RB == 128) launch_rb<T, 128>(ctx, q, K, V, idx, k, scale, nsplit);
+        else if (RB == 64) launch_rb<T, 64>(ctx, q, K, V, idx, k, scale, nsplit);
+        else launch_rb<T, 32>(ctx, q, K, V, idx, k, scale, nsplit);
+        if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
+    }
+    StageTimer timer(ctx, SPOTLIGHT_STAGE_MERGE);
     hipLaunchKernelGGL(merge_kernel, dim3(kHeadDim / kMergeCols, static_cast<unsigned>(heads)), dim3(kThreads), 0, ctx->stream,
                        reinterpret_cast<const float2*>(ctx->workspace + p.off_part_ml),
                        reinterpret_cast<const float*>(ctx->workspace + p.off_part_acc), out, nsplit, p.max_splits);
