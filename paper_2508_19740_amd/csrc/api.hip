@@ -73,15 +73,7 @@ StageTimer::StageTimer(spotlight_ctx* c, int stage) : ctx(c), rec(nullptr)
         c->n_events = c->n_rec + 1;
     }
     r->stage = stage;
-    if (hipEventRecord(r->start, c->stream) != hipSuccess) return;
     rec = r;
-}
-
-StageTimer::~StageTimer()
-{
-    if (!rec) return;
-    (void)hipEventRecord(rec->stop, ctx->stream);
-    ctx->n_rec += 1;
 }
 
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }

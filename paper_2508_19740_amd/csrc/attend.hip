@@ -245,16 +245,15 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(const float2* __restric
 }
 
 template <typename T, int RB>
-void launch_rb(spotlight_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* idx, int k,
-               float scale, int nsplit)
+void launch_rb(spotlight_ctx* ctx, StageTimer& timer, const void* q, const void* K, const void* V, const int32_t* idx,
+               int k, float scale, int nsplit)
 {
     const Plan& p = ctx->plan;
     dim3 grid(static_cast<unsigned>(nsplit), static_cast<unsigned>(p.B * p.Hq));
-    hipLaunchKernelGGL((attend_kernel<T, RB>), grid, dim3(kThreads), 0, ctx->stream, static_cast<const T*>(q),
-                       static_cast<const T*>(K), static_cast<const T*>(V), idx,
-                       reinterpret_cast<float2*>(ctx->workspace + p.off_part_ml),
-                       reinterpret_cast<float*>(ctx->workspace + p.off_part_acc), k, scale, p.Nmax, p.Hq, p.Hkv,
-                       nsplit, p.max_splits);
+    timer.launch(attend_kernel<T, RB>, grid, dim3(kThreads), 0, static_cast<const T*>(q), static_cast<const T*>(K),
+                 static_cast<const T*>(V), idx, reinterpret_cast<float2*>(ctx->workspace + p.off_part_ml),
+                 reinterpret_cast<float*>(ctx->workspace + p.off_part_acc), k, scale, p.Nmax, p.Hq, p.Hkv, nsplit,
+                 p.max_splits);
 }
 
 template <typename T>
@@ -269,15 +268,15 @@ int launch_t(spotlight_ctx* ctx, const void* q, const void* K, const void* V, co
     const int nsplit = (k + RB - 1) / RB;
     {
         StageTimer timer(ctx, SPOTLIGHT_STAGE_ATTEND);
-        if (RB == 128) launch_rb<T, 128>(ctx, q, K, V, idx, k, scale, nsplit);
-        else if (RB == 64) launch_rb<T, 64>(ctx, q, K, V, idx, k, scale, nsplit);
-        else launch_rb<T, 32>(ctx, q, K, V, idx, k, scale, nsplit);
+        if (RB == 128) launch_rb<T, 128>(ctx, timer, q, K, V, idx, k, scale, nsplit);
+        else if (RB == 64) launch_rb<T, 64>(ctx, timer, q, K, V, idx, k, scale, nsplit);
+        else launch_rb<T, 32>(ctx, timer, q, K, V, idx, k, scale, nsplit);
         if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
     }
     StageTimer timer(ctx, SPOTLIGHT_STAGE_MERGE);
-    hipLaunchKernelGGL(merge_kernel, dim3(kHeadDim / kMergeCols, static_cast<unsigned>(heads)), dim3(kThreads), 0, ctx->stream,
-                       reinterpret_cast<const float2*>(ctx->workspace + p.off_part_ml),
-                       reinterpret_cast<const float*>(ctx->workspace + p.off_part_acc), out, nsplit, p.max_splits);
+    timer.launch(merge_kernel, dim3(kHeadDim / kMergeCols, static_cast<unsigned>(heads)), dim3(kThreads), 0,
+                 reinterpret_cast<const float2*>(ctx->workspace + p.off_part_ml),
+                 reinterpret_cast<const float*>(ctx->workspace + p.off_part_acc), out, nsplit, p.max_splits);
     return hip_rc(hipGetLastError());
 }
 

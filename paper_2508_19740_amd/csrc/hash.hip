@@ -672,7 +672,7 @@ int run_vec(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, const HashArgs*
     auto kern = hash_vec_kernel<XT, WT, false>;
     if (packed) kern = hash_vec_kernel<XT, WT, true>;
     StageTimer timer(ctx, stage);
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), lds, ctx->stream, jobs);
+    timer.launch(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), lds, jobs);
     return hip_rc(hipGetLastError());
 }
 
@@ -692,7 +692,7 @@ int run(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
     const int64_t tiles = (a.n_rows + TK - 1) / TK;
     dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(n_xheads));
     StageTimer timer(ctx, stage);
-    hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, ctx->stream, a);
+    timer.launch(kern, grid, dim3(kThreads), lds, a);
     return hip_rc(hipGetLastError());
 }
 
@@ -727,11 +727,11 @@ int run_mfma_nbw(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage,
     // error bound per unit of ||W2[j]|| * ||h||, see the kernel's header
     const double eps = 1.01 * (a.hidden * (0x1p-24 + 1.01 * 0x1p-22) + 0x1p-17);
     dim3 grid(static_cast<unsigned>((tiles + tpg - 1) / tpg), static_cast<unsigned>(n_xheads));
-    StageTimer timer(ctx, stage);
     const int n_out = a.n_wheads * a.L;
     hipLaunchKernelGGL(w2_norm_kernel, dim3(static_cast<unsigned>((n_out + kThreads - 1) / kThreads)), dim3(kThreads), 0,
-                       ctx->stream, static_cast<const bf16_raw*>(a.w2), wnorm, n_out, a.hidden);
-    hipLaunchKernelGGL(kern, grid, dim3(kThreads), lds, ctx->stream, a, wnorm, static_cast<float>(eps), tpg);
+                       ctx->stream, static_cast<const bf16_raw*>(a.w2), wnorm, n_out, a.hidden);   // microseconds: not timed
+    StageTimer timer(ctx, stage);
+    timer.launch(kern, grid, dim3(kThreads), lds, a, wnorm, static_cast<float>(eps), tpg);
     return hip_rc(hipGetLastError());
 }
 

@@ -2,6 +2,9 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#if defined(__HIPCC__)
+#include <hip/hip_ext.h>
+#endif
 #include <stdint.h>
 
 #include "spotlight.h"
@@ -95,12 +98,26 @@ struct spotlight_ctx {
 
 namespace spotlight {
 
-// RAII bracket around one kernel launch: records events when profiling is on.
+// One timed kernel launch.  With profiling on, the launch carries a pair of events that the
+// runtime stamps when the kernel starts and when it ends (so the difference is the kernel's own
+// duration, without the gaps around it); with profiling off it is a plain launch.
 struct StageTimer {
     spotlight_ctx* ctx;
     ProfileRec* rec;
     StageTimer(spotlight_ctx* c, int stage);
-    ~StageTimer();
+#if defined(__HIPCC__)
+    template <typename F, typename... Args>
+    void launch(F kernel, const dim3& grid, const dim3& block, size_t lds, Args... args)
+    {
+        if (rec) {
+            hipExtLaunchKernelGGL(kernel, grid, block, static_cast<uint32_t>(lds), ctx->stream, rec->start, rec->stop, 0, args...);
+            ctx->n_rec += 1;
+            rec = nullptr;   // one launch per record
+        } else {
+            hipLaunchKernelGGL(kernel, grid, block, lds, ctx->stream, args...);
+        }
+    }
+#endif
 };
 
 // Launchers (each returns SPOTLIGHT_OK or SPOTLIGHT_ERR_*).  All pointers are device pointers.

@@ -703,7 +703,7 @@ struct RetrieveArgs {
 };
 
 template <int W, int G>
-int launch_score_wg(spotlight_ctx* ctx, const RetrieveArgs& a, int* tasks_per_group)
+int launch_score_wg(spotlight_ctx* ctx, StageTimer& timer, const RetrieveArgs& a, int* tasks_per_group)
 {
     const Plan& p = ctx->plan;
     constexpr int BINS = W * 32 + 2;
@@ -751,7 +751,7 @@ int launch_score_wg(spotlight_ctx* ctx, const RetrieveArgs& a, int* tasks_per_gr
     if (s.tasks_per_group >= kLongRun) s.tasks_per_group = kShortRun;
     *tasks_per_group = s.tasks_per_group;
     const int grid = (s.total_tasks + s.tasks_per_group - 1) / s.tasks_per_group;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), 0, ctx->stream, s);
+    timer.launch(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), 0, s);
     return SPOTLIGHT_OK;
 }
 
@@ -766,14 +766,14 @@ int launch_w(spotlight_ctx* ctx, const RetrieveArgs& a)
         StageTimer timer(ctx, SPOTLIGHT_STAGE_SCORE);
         int rc;
         switch (p.G) {
-        case 1: rc = launch_score_wg<W, 1>(ctx, a, &tasks_per_group); break;
-        case 2: rc = launch_score_wg<W, 2>(ctx, a, &tasks_per_group); break;
+        case 1: rc = launch_score_wg<W, 1>(ctx, timer, a, &tasks_per_group); break;
+        case 2: rc = launch_score_wg<W, 2>(ctx, timer, a, &tasks_per_group); break;
         case 4:
             // 1024-bit codes: the histograms of more than two heads do not fit in LDS
-            if constexpr (W <= 16) { rc = launch_score_wg<W, 4>(ctx, a, &tasks_per_group); break; }
+            if constexpr (W <= 16) { rc = launch_score_wg<W, 4>(ctx, timer, a, &tasks_per_group); break; }
             return SPOTLIGHT_ERR_UNSUPPORTED;
         case 8:
-            if constexpr (W <= 16) { rc = launch_score_wg<W, 8>(ctx, a, &tasks_per_group); break; }
+            if constexpr (W <= 16) { rc = launch_score_wg<W, 8>(ctx, timer, a, &tasks_per_group); break; }
             return SPOTLIGHT_ERR_UNSUPPORTED;
         default: return SPOTLIGHT_ERR_UNSUPPORTED;
         }
@@ -790,12 +790,12 @@ int launch_w(spotlight_ctx* ctx, const RetrieveArgs& a)
         if (forced && !narrow) kern = select_kernel<W, true, kSelThreads>;
         if (!forced && narrow) kern = select_kernel<W, false, kSelThreadsNarrow>;
         if (forced && narrow) kern = select_kernel<W, true, kSelThreadsNarrow>;
-        hipLaunchKernelGGL(kern, grid, dim3(narrow ? kSelThreadsNarrow : kSelThreads), 0, ctx->stream, a.codes, qcode,
-                           reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_gcum),
-                           reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_blockcum),
-                           reinterpret_cast<const BlockMeta*>(ctx->workspace + p.off_blockmeta),
-                           reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_cand), a.out_idx, a.n_tokens,
-                           p.Nmax, p.Hq, p.Hkv, p.max_blocks, a.k, a.n_sink, a.local_begin, tasks_per_group);
+        timer.launch(kern, grid, dim3(narrow ? kSelThreadsNarrow : kSelThreads), 0, a.codes, qcode,
+                     reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_gcum),
+                     reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_blockcum),
+                     reinterpret_cast<const BlockMeta*>(ctx->workspace + p.off_blockmeta),
+                     reinterpret_cast<const uint32_t*>(ctx->workspace + p.off_cand), a.out_idx, a.n_tokens, p.Nmax,
+                     p.Hq, p.Hkv, p.max_blocks, a.k, a.n_sink, a.local_begin, tasks_per_group);
         if (hipGetLastError() != hipSuccess) return SPOTLIGHT_ERR_HIP;
     }
     if (a.out_dist) {
