@@ -25,3 +25,13 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_runtest_logstart(nodeid, location):
+    """A GPU run names each test, flushed, before it starts: the full-size tests take a minute
+    each, and when a kernel faults the last line says which case it was."""
+    item_is_gpu = "test_gpu_" in nodeid
+    if not item_is_gpu:
+        return
+    sys.__stderr__.write(f"[gpu test] {nodeid}\n")
+    sys.__stderr__.flush()
