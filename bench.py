@@ -57,6 +57,8 @@ def main():
         sys.exit(2)
 
     import torch
+    import __graft_entry__
+    __graft_entry__.ensure_built()   # builds only if the tree holds no library
     import workload as wl
     import paper_2508_19740_amd as sp
 
