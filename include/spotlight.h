@@ -198,9 +198,10 @@ int spotlight_decode_step(spotlight_ctx *ctx, const void *q, const void *K, cons
 
 /*
  * Stage timing for benchmarks.  While enabled, every kernel launch carries two HIP events that are
- * stamped when the kernel starts and when it ends.  spotlight_profile_read waits for the stream, adds the elapsed times of
- * the launches recorded since the last read to the per-stage totals and returns the totals for
- * `stage` (milliseconds, number of launches).  spotlight_profile_enable(ctx, 0) stops recording
+ * stamped when the kernel starts and when it ends.  spotlight_profile_read waits for the stream,
+ * adds the elapsed times of the launches recorded since the last read to the per-stage totals and
+ * returns the totals for `stage` (milliseconds, number of launches).  Do not capture into a HIP
+ * graph while it is enabled.  spotlight_profile_enable(ctx, 0) stops recording
  * and clears the totals.  At most 8192 launches are recorded between two reads; later ones are
  * not timed.
  */
