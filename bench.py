@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--code-bits", type=int, default=0, help="override the workload's code length L")
     ap.add_argument("--hidden", type=int, default=-1, help="override the hash MLP's hidden width (0 = linear hash sign(xR))")
     ap.add_argument("--lsh-init", default="", help="linear hash only: gaussian | rotation")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--no-prepack", action="store_true",
                     help="hash from the weight arrays as stored (no packed copy in the contexts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -78,6 +79,9 @@ def main():
     if args.lsh_init:
         cfg = cfg.scaled(lsh_init=args.lsh_init)
         variant += f", {args.lsh_init} LSH"
+    if args.batch > 0:
+        cfg = cfg.scaled(batch=args.batch)
+        variant += f", batch={args.batch}"
     B, Hq, Hkv, N, L, W, k, d = (cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_tokens, cfg.code_bits,
                                  cfg.words, cfg.topk, cfg.head_dim)
     esz = 2 if cfg.kv_dtype == "bf16" else 4
