@@ -57,6 +57,18 @@ enum {
     SPOTLIGHT_STAGE_COUNT = 6
 };
 
+/* Switches of a context, for spotlight_set_option. */
+enum {
+    /* 1 (default): a bulk spotlight_hash_keys call with bfloat16 weights evaluates the second hash
+     * layer on the matrix cores (same codes, see spotlight_hash_keys); 0: everything on the binary32
+     * fused-multiply-add chain. */
+    SPOTLIGHT_OPT_BULK_HASH_MATRIX_CORES = 0,
+    /* 1: the matrix-core bulk hash also evaluates EVERY output with the chain and records how far
+     * the two results are apart (spotlight_bulk_hash_audit_read).  Slow; for tests.  Default 0. */
+    SPOTLIGHT_OPT_BULK_HASH_AUDIT = 1,
+    SPOTLIGHT_OPT_COUNT = 2
+};
+
 typedef struct {
     int32_t batch;        /* B  >= 1                                                     */
     int32_t n_q_heads;    /* Hq >= 1, multiple of n_kv_heads, Hq / Hkv <= 8              */
@@ -103,6 +115,13 @@ int spotlight_set_stream(spotlight_ctx *ctx, void *stream);
 /* Static text for a return code. */
 const char *spotlight_strerror(int rc);
 
+/* "SPOTLIGHT_BUILD_ID=" followed by the hash of the sources this library was compiled from. */
+const char *spotlight_build_id(void);
+
+/* Sets a SPOTLIGHT_OPT_* switch of the context.  Host only.  Errors: INVALID_ARG for a NULL context,
+ * an unknown option or a value other than 0 / 1. */
+int spotlight_set_option(spotlight_ctx *ctx, int option, int value);
+
 /*
  * Optional, for callers whose hash weights stay put (inference): copies the weights into the
  * context's workspace in the order the kernel that hashes ONE vector per head reads them, so that
@@ -126,8 +145,8 @@ int spotlight_prepack_weights(spotlight_ctx *ctx, const spotlight_hash_weights *
  * The codes are those of IEEE binary32 arithmetic with one fused multiply-add chain per output
  * in increasing index order, so they do not depend on launch shape.  (With bfloat16 weights a
  * bulk call evaluates the second layer on the matrix cores and recomputes, with that chain, every
- * output whose sign the matrix-core result does not settle: same bits.  Setting
- * SPOTLIGHT_NO_MFMA in the environment keeps everything on the chain.)
+ * output whose sign the matrix-core result does not settle: same bits.
+ * SPOTLIGHT_OPT_BULK_HASH_MATRIX_CORES = 0 keeps everything on the chain.)
  *
  *   K      [B, Hkv, Nmax, d]  kv_dtype   read rows t0 .. t0+n_new-1 of every head
  *   codes  [B, Hkv, Nmax, W]  uint32     those rows written, all others untouched
@@ -136,6 +155,21 @@ int spotlight_prepack_weights(spotlight_ctx *ctx, const spotlight_hash_weights *
  */
 int spotlight_hash_keys(spotlight_ctx *ctx, const void *K, const spotlight_hash_weights *w,
                         int64_t t0, int64_t n_new, uint32_t *codes);
+
+/*
+ * Evidence for the bound behind the matrix-core bulk hash.  With SPOTLIGHT_OPT_BULK_HASH_AUDIT on,
+ * every bulk spotlight_hash_keys call that takes the matrix-core path adds to four totals kept in
+ * the workspace; this call waits for the stream, returns them and clears them (NULL outputs are
+ * skipped):
+ *   outputs    hash outputs (key x code bit) evaluated on the matrix cores
+ *   listed     of those, outputs whose sign the error bound did not settle (recomputed on the chain)
+ *   wrong      outputs the bound did settle whose sign differs from the chain's; the method relies
+ *              on this being 0
+ *   max_ratio  largest |y_matrix - y_chain| / (||W2[j]|| ||h||) seen; the bound assumes it stays
+ *              below eps = 1.01 (h (2^-24 + 1.01 2^-22) + 2^-17), returned in *eps
+ */
+int spotlight_bulk_hash_audit_read(spotlight_ctx *ctx, int64_t *outputs, int64_t *listed, int64_t *wrong,
+                                   double *max_ratio, double *eps);
 
 /*
  * Hash the queries (Eq. 5-6), score every cached key code of the head by Hamming distance

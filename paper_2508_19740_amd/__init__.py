@@ -6,7 +6,9 @@ been built; there is no CPU or eager fallback.
 """
 from .binding import (  # noqa: F401
     Spotlight, SpotlightError, Config, HashWeights, make_config, validate_config, workspace_bytes,
-    token_budget, spotlight_hash_keys, spotlight_retrieve_topk, spotlight_sparse_decode, spotlight_decode_step,
+    spotlight_hash_keys, spotlight_retrieve_topk, spotlight_sparse_decode, spotlight_decode_step,
     spotlight_prepack_weights, lib, SYMBOLS,
+    build_id, OPT_BULK_HASH_MATRIX_CORES, OPT_BULK_HASH_AUDIT,
     STAGES, OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, F32, BF16,
 )
+from .policy import token_budget  # noqa: F401,E402

@@ -23,8 +23,9 @@ SYMBOLS = (
     "spotlight_validate_config", "spotlight_workspace_bytes", "spotlight_create", "spotlight_destroy",
     "spotlight_set_stream", "spotlight_strerror", "spotlight_hash_keys", "spotlight_retrieve_topk",
     "spotlight_sparse_decode", "spotlight_decode_step", "spotlight_prepack_weights", "spotlight_profile_enable",
-    "spotlight_profile_read",
+    "spotlight_profile_read", "spotlight_build_id", "spotlight_set_option", "spotlight_bulk_hash_audit_read",
 )
+OPT_BULK_HASH_MATRIX_CORES, OPT_BULK_HASH_AUDIT = 0, 1
 
 
 class Config(C.Structure):
@@ -63,6 +64,11 @@ def _load() -> C.CDLL:
     lib.spotlight_prepack_weights.argtypes = [vp, C.POINTER(HashWeights)]
     lib.spotlight_profile_enable.argtypes = [vp, C.c_int]
     lib.spotlight_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
+    lib.spotlight_build_id.argtypes = []
+    lib.spotlight_build_id.restype = C.c_char_p
+    lib.spotlight_set_option.argtypes = [vp, C.c_int, C.c_int]
+    lib.spotlight_bulk_hash_audit_read.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64),
+                                                   C.POINTER(C.c_double), C.POINTER(C.c_double)]
     return lib
 
 
@@ -97,11 +103,9 @@ def workspace_bytes(cfg: Config) -> int:
     return lib.spotlight_workspace_bytes(C.byref(cfg))
 
 
-def token_budget(n_tokens: int, pruning_rate: float, minimum: int = 20) -> int:
-    """Caller-side policy for k (paper appendix, language-modeling details): the kept share of the
-    sequence rounded down, but at least `minimum` tokens; 98 % pruning gives 81 of 4096, 163 of 8192."""
-    kept = int(math.floor(n_tokens * (1.0 - pruning_rate) + 1e-9))
-    return max(minimum, kept)
+def build_id() -> str:
+    """Hash of the sources the loaded library was compiled from."""
+    return lib.spotlight_build_id().decode().split("=", 1)[1]
 
 
 class Spotlight:
@@ -157,6 +161,20 @@ class Spotlight:
         if s != self.cfg.stream:
             self.cfg.stream = s
             lib.spotlight_set_stream(self._h, s)
+
+    def set_option(self, option: int, value: int):
+        rc = lib.spotlight_set_option(self._h, option, value)
+        if rc != OK:
+            raise SpotlightError(rc, "spotlight_set_option")
+
+    def bulk_hash_audit_read(self) -> dict:
+        """Totals of the audited matrix-core bulk hash since the last read (and clears them)."""
+        n, li, wr = C.c_int64(), C.c_int64(), C.c_int64()
+        ratio, eps = C.c_double(), C.c_double()
+        rc = lib.spotlight_bulk_hash_audit_read(self._h, C.byref(n), C.byref(li), C.byref(wr), C.byref(ratio), C.byref(eps))
+        if rc != OK:
+            raise SpotlightError(rc, "spotlight_bulk_hash_audit_read")
+        return {"outputs": n.value, "listed": li.value, "wrong": wr.value, "max_ratio": ratio.value, "eps": eps.value}
 
     # ------------------------------------------------------------------ entry points
     def prepack_weights(self, w1=None, b1=None, w2=None):

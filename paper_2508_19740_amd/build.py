@@ -1,4 +1,9 @@
-"""Compile the HIP library for gfx950 into paper_2508_19740_amd/libspotlight.so (in-tree)."""
+"""Compile the HIP library for gfx950 into paper_2508_19740_amd/libspotlight.so (in-tree).
+
+The library carries the hash of the sources it was built from (spotlight_build_id); stale()
+compares it with the sources in the tree, so a library older than its sources is rebuilt, not run.
+"""
+import hashlib
 import os
 import subprocess
 
@@ -6,52 +11,97 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.environ.get("SPOTLIGHT_LIB") or os.path.join(HERE, "libspotlight.so")
-SOURCES = ["api.hip", "hash.hip", "retrieve.hip", "attend.hip"]
+OBJDIR = os.path.join(HERE, "_build")          # object files of the last build (not tracked)
+HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "retrieve_kernels.h"),
+           os.path.join(ROOT, "include", "spotlight.h")]
+ID_MARK = "SPOTLIGHT_BUILD_ID="
 
 # -ffp-contract=off: the hash codes are defined by an exact sequence of binary32 operations, so
 #   only the fused multiply-adds written out in the source may be fused.
 # -packed-fp32-ops off: the compiler must not form packed binary32 instructions.
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes"]
 
 
 def sources():
-    return [os.path.join(CSRC, s) for s in SOURCES]
+    return sorted(os.path.join(CSRC, s) for s in os.listdir(CSRC) if s.endswith(".hip"))
+
+
+def _digest(paths, extra=""):
+    h = hashlib.sha256(extra.encode())
+    for p in paths:
+        h.update(os.path.basename(p).encode())
+        with open(p, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def source_id() -> str:
+    """Hash of every source, header and compiler flag the library is built from."""
+    return _digest(sources() + [h for h in HEADERS if os.path.exists(h)], " ".join(FLAGS))
+
+
+def built_id(path: str = None):
+    """The source hash recorded inside a built library (read from the file, not by loading it)."""
+    path = path or LIB
+    if not os.path.exists(path):
+        return None
+    with open(path, "rb") as f:
+        blob = f.read()
+    at = blob.find(ID_MARK.encode())
+    if at < 0:
+        return None
+    return blob[at + len(ID_MARK):at + len(ID_MARK) + 16].decode(errors="replace")
 
 
 def stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "internal.h"), os.path.join(ROOT, "include", "spotlight.h")]
-    return any(os.path.getmtime(d) > t for d in deps)
+    return built_id() != source_id()
 
 
-def build(verbose: bool = False) -> str:
-    """One hipcc per source file, side by side, then the link."""
+def build(verbose: bool = False, force: bool = True) -> str:
+    """One hipcc per source file, side by side, then the link.  With force=False the object files
+    of sources that have not changed since the last build are reused."""
     import concurrent.futures
-    import tempfile
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    compile_flags = [f for f in FLAGS if f != "-shared"]
-    with tempfile.TemporaryDirectory(prefix="spotlight_build_") as tmp:
-        objs = [os.path.join(tmp, os.path.basename(src) + ".o") for src in sources()]
+    os.makedirs(OBJDIR, exist_ok=True)
+    sid = source_id()
+    headers = [h for h in HEADERS if os.path.exists(h)]
+    jobs = []
+    objs = []
+    for src in sources():
+        key = _digest([src] + headers, " ".join(FLAGS) + sid * (os.path.basename(src) == "api.hip"))
+        obj = os.path.join(OBJDIR, os.path.basename(src) + ".o")
+        objs.append(obj)
+        tag = obj + ".key"
+        have = open(tag).read() if os.path.exists(tag) and os.path.exists(obj) else None
+        if force or have != key:
+            jobs.append((src, obj, tag, key))
 
-        def compile_one(pair):
-            src, obj = pair
-            cmd = [hipcc, *compile_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj]
-            if verbose:
-                print(" ".join(cmd))
-            subprocess.run(cmd, check=True)
-
-        with concurrent.futures.ThreadPoolExecutor(max_workers=len(objs)) as pool:
-            list(pool.map(compile_one, zip(sources(), objs)))
-        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    def compile_one(job):
+        src, obj, tag, key = job
+        if os.path.exists(tag):
+            os.remove(tag)
+        cmd = [hipcc, *FLAGS, f'-DSPOTLIGHT_BUILD_ID_STRING="{ID_MARK}{sid}"', "-I", os.path.join(ROOT, "include"),
+               "-I", CSRC, "-c", src, "-o", obj]
         if verbose:
-            print(" ".join(cmd))
+            print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
+        with open(tag, "w") as f:
+            f.write(key)
+
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, max(1, len(jobs)))) as pool:
+        list(pool.map(compile_one, jobs))
+    # stale objects of sources that no longer exist must not be linked
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB + ".tmp", *objs]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    os.replace(LIB + ".tmp", LIB)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose=True, force="--incremental" not in sys.argv))
+    print("build id", built_id())

@@ -59,6 +59,7 @@ int make_plan(const spotlight_config* c, Plan* p)
     const size_t welem = p->w_dtype == SPOTLIGHT_BF16 ? 2 : 4;
     p->off_pack_w1 = off;   off = align_up(off + static_cast<size_t>(p->Hkv) * p->pack_w1_elems * welem, 256);
     p->off_pack_out = off;  off = align_up(off + static_cast<size_t>(p->Hkv) * p->pack_out_elems * welem, 256);
+    p->off_audit = off;     off = align_up(off + sizeof(AuditRec), 256);
     p->total_bytes = off;
     return SPOTLIGHT_OK;
 }
@@ -74,6 +75,19 @@ StageTimer::StageTimer(spotlight_ctx* c, int stage) : ctx(c), rec(nullptr)
     }
     r->stage = stage;
     rec = r;
+}
+
+int allow_dynamic_lds(spotlight_ctx* ctx, const void* kernel, size_t bytes)
+{
+    if (bytes <= 48 * 1024) return SPOTLIGHT_OK;
+    for (int i = 0; i < ctx->n_big_lds_kernels; ++i)
+        if (ctx->big_lds_kernels[i] == kernel) return SPOTLIGHT_OK;
+    // the limit is raised to all the LDS a workgroup may have, so that one call serves every later size
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, ctx->max_lds) != hipSuccess)
+        return SPOTLIGHT_ERR_HIP;
+    const int cap = static_cast<int>(sizeof(ctx->big_lds_kernels) / sizeof(ctx->big_lds_kernels[0]));
+    if (ctx->n_big_lds_kernels < cap) ctx->big_lds_kernels[ctx->n_big_lds_kernels++] = kernel;
+    return SPOTLIGHT_OK;
 }
 
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -141,6 +155,7 @@ int spotlight_create(spotlight_ctx** out, const spotlight_config* cfg)
     }
     ctx->max_lds = lds;
     ctx->n_cus = cus;
+    ctx->opt[SPOTLIGHT_OPT_BULK_HASH_MATRIX_CORES] = 1;
     void* ws = nullptr;
     if (hipMalloc(&ws, plan.total_bytes) != hipSuccess) {
         (void)hipGetLastError();
@@ -149,6 +164,12 @@ int spotlight_create(spotlight_ctx** out, const spotlight_config* cfg)
         return SPOTLIGHT_ERR_WORKSPACE;
     }
     ctx->workspace = static_cast<char*>(ws);
+    if (hipMemsetAsync(ctx->workspace + plan.off_audit, 0, sizeof(AuditRec), ctx->stream) != hipSuccess) {
+        (void)hipFree(ws);
+        delete[] ctx->recs;
+        delete ctx;
+        return SPOTLIGHT_ERR_HIP;
+    }
     *out = ctx;
     return SPOTLIGHT_OK;
 }
@@ -165,6 +186,40 @@ int spotlight_destroy(spotlight_ctx* ctx)
     delete[] ctx->recs;
     delete ctx;
     return rc;
+}
+
+#ifndef SPOTLIGHT_BUILD_ID_STRING
+#define SPOTLIGHT_BUILD_ID_STRING "SPOTLIGHT_BUILD_ID=unknown"
+#endif
+const char* spotlight_build_id(void) { return SPOTLIGHT_BUILD_ID_STRING; }
+
+int spotlight_set_option(spotlight_ctx* ctx, int option, int value)
+{
+    if (!ctx || option < 0 || option >= SPOTLIGHT_OPT_COUNT || (value != 0 && value != 1)) return SPOTLIGHT_ERR_INVALID_ARG;
+    ctx->opt[option] = value;
+    return SPOTLIGHT_OK;
+}
+
+int spotlight_bulk_hash_audit_read(spotlight_ctx* ctx, int64_t* outputs, int64_t* listed, int64_t* wrong,
+                                   double* max_ratio, double* eps)
+{
+    if (!ctx) return SPOTLIGHT_ERR_INVALID_ARG;
+    AuditRec rec;
+    char* dev = ctx->workspace + ctx->plan.off_audit;
+    if (hipMemcpyAsync(&rec, dev, sizeof(rec), hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+        hipMemsetAsync(dev, 0, sizeof(rec), ctx->stream) != hipSuccess ||
+        hipStreamSynchronize(ctx->stream) != hipSuccess)
+        return SPOTLIGHT_ERR_HIP;
+    if (outputs) *outputs = static_cast<int64_t>(rec.outputs);
+    if (listed) *listed = static_cast<int64_t>(rec.listed);
+    if (wrong) *wrong = static_cast<int64_t>(rec.wrong);
+    if (max_ratio) {
+        float f;
+        memcpy(&f, &rec.max_ratio_bits, sizeof(f));
+        *max_ratio = f;
+    }
+    if (eps) *eps = bulk_hash_eps(ctx->plan.hidden);
+    return SPOTLIGHT_OK;
 }
 
 int spotlight_set_stream(spotlight_ctx* ctx, void* stream)
@@ -208,7 +263,8 @@ static HashLaunch key_job(const spotlight_ctx* ctx, const void* K, const spotlig
     h.code_row0 = t0;
     h.zero = nullptr;
     h.zero_words = 0;
-    h.wnorm = reinterpret_cast<float*>(ctx->workspace + p.off_wnorm);
+    h.wnorm = ctx->opt[SPOTLIGHT_OPT_BULK_HASH_MATRIX_CORES] ? reinterpret_cast<float*>(ctx->workspace + p.off_wnorm) : nullptr;
+    h.audit = ctx->opt[SPOTLIGHT_OPT_BULK_HASH_AUDIT] ? reinterpret_cast<AuditRec*>(ctx->workspace + p.off_audit) : nullptr;
     attach_packed(ctx, w, &h);
     return h;
 }
@@ -239,6 +295,7 @@ static HashLaunch query_job(const spotlight_ctx* ctx, const void* q, const spotl
     h.zero = reinterpret_cast<uint32_t*>(ctx->workspace + p.off_gcum);
     h.zero_words = p.L + 2;
     h.wnorm = nullptr;
+    h.audit = nullptr;
     attach_packed(ctx, w, &h);
     return h;
 }

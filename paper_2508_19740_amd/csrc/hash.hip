@@ -14,8 +14,6 @@
 //          ballot of (y > 0) IS the pair of packed words.  No boolean tensor is ever stored.
 #include "internal.h"
 
-#include <stdlib.h>
-
 namespace spotlight {
 namespace {
 
@@ -118,6 +116,7 @@ struct HashArgs {
     uint32_t* zero;
     int zero_words;
     float* wnorm;   // scratch for the output-row norms of the matrix-core path, or null
+    AuditRec* audit;   // totals of the audited matrix-core path, or null
     const void* pack_w1;   // packed copies for the single-vector kernel, or null
     const void* pack_out;
 };
@@ -305,7 +304,10 @@ __global__ __launch_bounds__(kThreads) void w2_norm_kernel(const bf16_raw* __res
 }
 
 // NBW: code words (MFMA column blocks) per wavefront = ceil(W / 4).
-template <typename XT, int NBW>
+// AUDIT: every output is also evaluated with the canonical chain and compared with the matrix
+// cores' value (distance in units of ||W2[j]|| ||h||, settled signs that disagree); the totals go to
+// a.audit.  The codes written are the same either way.
+template <typename XT, int NBW, bool AUDIT>
 __global__ __launch_bounds__(kThreads) void hash_mfma_kernel(HashArgs a, const float* __restrict__ wnorm, float eps,
                                                             int tiles_per_group)
 {
@@ -325,6 +327,9 @@ __global__ __launch_bounds__(kThreads) void hash_mfma_kernel(HashArgs a, const f
     const WT* b1 = static_cast<const WT*>(a.b1) + static_cast<int64_t>(whead) * a.hidden;
     const WT* w2 = static_cast<const WT*>(a.w2) + static_cast<int64_t>(whead) * a.L * a.hidden;
     const int n8 = a.hidden / 8;
+
+    uint32_t au_outputs = 0, au_listed = 0, au_wrong = 0;   // this lane's audit totals
+    float au_ratio = 0.0f;
 
     const int64_t n_tiles = (a.n_rows + TK - 1) / TK;
     const int64_t tile0 = static_cast<int64_t>(blockIdx.x) * tiles_per_group;
@@ -413,6 +418,45 @@ __global__ __launch_bounds__(kThreads) void hash_mfma_kernel(HashArgs a, const f
             }
         }
 
+        if constexpr (AUDIT) {
+            // the canonical chain for each of this lane's outputs: its 16 vectors share the weight row
+#pragma unroll 1
+            for (int nb = 0; nb < NBW; ++nb) {
+                const int word = wave + 4 * nb;
+                if (word >= a.W) continue;
+                const int j = (31 - c) * a.W + word;
+                const WT* row = w2 + static_cast<int64_t>(j) * a.hidden;
+                float yc[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) yc[v] = 0.0f;
+                for (int g = 0; g < n8; ++g) {
+                    float wv[8];
+                    load8(row + g * 8, wv);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            yc[v] = __builtin_fmaf(wv[q], hs[(g * 8 + q) * TK + (v / 4) * 8 + half * 4 + (v % 4)], yc[v]);
+                }
+                const float tcol = eps * wn[j];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int t = (v / 4) * 8 + half * 4 + (v % 4);
+                    if (t >= rows) continue;
+                    const float y = acc[nb][v];
+                    const bool sure = __builtin_fabsf(y) > __builtin_fmaf(tcol, hn[t], 1e-30f);
+                    const float den = wn[j] * hn[t];
+                    const float diff = __builtin_fabsf(y - yc[v]);
+                    // a NaN or an infinity on either side is never settled and is not a distance
+                    const float ratio = (diff == 0.0f || !(diff < INFINITY)) ? 0.0f : (den > 0.0f ? diff / den : INFINITY);
+                    au_ratio = fmaxf(au_ratio, ratio);
+                    au_outputs += 1;
+                    au_listed += sure ? 0 : 1;
+                    au_wrong += (sure && ((y > 0.0f) != (yc[v] > 0.0f))) ? 1 : 0;
+                }
+            }
+        }
+
         // ---- signs, ballot-pack, and the list of outputs too close to zero to trust
 #pragma unroll
         for (int nb = 0; nb < NBW; ++nb) {
@@ -473,6 +517,17 @@ __global__ __launch_bounds__(kThreads) void hash_mfma_kernel(HashArgs a, const f
         // ---- the tile's codes: rows * W consecutive words
         uint32_t* cbase = a.codes + xhead * a.code_head_stride + (a.code_row0 + r0) * a.W;
         for (int e = tid; e < rows * a.W; e += kThreads) cbase[e] = m.codes[e / a.W][e % a.W];
+    }
+    if constexpr (AUDIT) {
+        const uint32_t outputs = wave_sum(au_outputs), listed = wave_sum(au_listed), wrong = wave_sum(au_wrong);
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) au_ratio = fmaxf(au_ratio, __shfl_xor(au_ratio, off));
+        if (lane == 0) {
+            atomicAdd(&a.audit->outputs, static_cast<unsigned long long>(outputs));
+            if (listed) atomicAdd(&a.audit->listed, static_cast<unsigned long long>(listed));
+            if (wrong) atomicAdd(&a.audit->wrong, static_cast<unsigned long long>(wrong));
+            atomicMax(&a.audit->max_ratio_bits, __float_as_uint(au_ratio));   // non-negative floats order like their bits
+        }
     }
 }
 
@@ -684,11 +739,7 @@ int run(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
     const size_t lds = lds_bytes(TK, a.hidden);
     if (lds > static_cast<size_t>(ctx->max_lds)) return SPOTLIGHT_ERR_UNSUPPORTED;
     auto kern = hash_kernel<XT, WT, TK, KSPLIT>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (e != hipSuccess) return SPOTLIGHT_ERR_HIP;
-    }
+    if (allow_dynamic_lds(ctx, reinterpret_cast<const void*>(kern), lds) != SPOTLIGHT_OK) return SPOTLIGHT_ERR_HIP;
     const int64_t tiles = (a.n_rows + TK - 1) / TK;
     dim3 grid(static_cast<unsigned>(tiles), static_cast<unsigned>(n_xheads));
     StageTimer timer(ctx, stage);
@@ -713,19 +764,15 @@ int run_ks(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
 template <typename XT, int NBW>
 int run_mfma_nbw(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage, size_t lds, float* wnorm)
 {
-    auto kern = hash_mfma_kernel<XT, NBW>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (e != hipSuccess) return SPOTLIGHT_ERR_HIP;
-    }
+    auto kern = hash_mfma_kernel<XT, NBW, false>;
+    if (a.audit) kern = hash_mfma_kernel<XT, NBW, true>;
+    if (allow_dynamic_lds(ctx, reinterpret_cast<const void*>(kern), lds) != SPOTLIGHT_OK) return SPOTLIGHT_ERR_HIP;
     const int64_t tiles = (a.n_rows + kMfmaTile - 1) / kMfmaTile;
     // a workgroup takes a run of tiles of one head (the output-row norms are computed once per run),
     // short enough that the grid still has a few thousand workgroups
     int tpg = 8;
     while (tpg > 1 && ((tiles + tpg - 1) / tpg) * n_xheads < 4096) tpg /= 2;
-    // error bound per unit of ||W2[j]|| * ||h||, see the kernel's header
-    const double eps = 1.01 * (a.hidden * (0x1p-24 + 1.01 * 0x1p-22) + 0x1p-17);
+    const double eps = bulk_hash_eps(a.hidden);   // error bound per unit of ||W2[j]|| * ||h||
     dim3 grid(static_cast<unsigned>((tiles + tpg - 1) / tpg), static_cast<unsigned>(n_xheads));
     const int n_out = a.n_wheads * a.L;
     hipLaunchKernelGGL(w2_norm_kernel, dim3(static_cast<unsigned>((n_out + kThreads - 1) / kThreads)), dim3(kThreads), 0,
@@ -752,7 +799,7 @@ int run_tk(spotlight_ctx* ctx, const HashArgs& a, int n_xheads, int stage)
     const size_t cap = static_cast<size_t>(ctx->max_lds);
     if constexpr (sizeof(WT) == 2) {
         if (a.n_rows >= kMfmaTile && a.hidden > 0 && a.hidden % 16 == 0 && a.W <= 16 &&
-            mfma_lds_bytes(a.hidden) <= cap && a.wnorm && !getenv("SPOTLIGHT_NO_MFMA"))
+            mfma_lds_bytes(a.hidden) <= cap && a.wnorm)
             return run_mfma<XT>(ctx, a, n_xheads, stage, a.wnorm);
     }
     // a single vector per head, hidden width a multiple of 128: the latency-oriented kernel
@@ -786,6 +833,7 @@ static HashArgs make_args(const HashLaunch& h)
     a.zero = h.zero;
     a.zero_words = h.zero_words;
     a.wnorm = h.wnorm;
+    a.audit = h.audit;
     a.pack_w1 = h.pack_w1;
     a.pack_out = h.pack_out;
     return a;

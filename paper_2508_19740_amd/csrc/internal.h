@@ -39,6 +39,7 @@ struct Plan {
     size_t off_pack_w1;    // first hash layer in the single-vector kernel's read order (pack_w1_elems per kv head)
     size_t off_pack_out;   // output matrix of the hash (W2, or R of the linear hash) in that order
     size_t pack_w1_elems, pack_out_elems;   // elements per kv head; both 0 if the hash shape has no such copy
+    size_t off_audit;      // AuditRec of the bulk hash (SPOTLIGHT_OPT_BULK_HASH_AUDIT)
     size_t total_bytes;
 };
 
@@ -69,6 +70,15 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t x)
 
 int make_plan(const spotlight_config* cfg, Plan* plan);  // SPOTLIGHT_OK or an error code; host only
 
+// What the audited bulk hash accumulates (device side), see spotlight_bulk_hash_audit_read.
+struct AuditRec {
+    unsigned long long outputs;    // hash outputs evaluated on the matrix cores
+    unsigned long long listed;     // of those, the ones whose sign the bound did not settle (recomputed)
+    unsigned long long wrong;      // outputs the bound settled whose sign differs from the chain's: must stay 0
+    uint32_t max_ratio_bits;       // largest |y_matrix - y_chain| / (||W2[j]|| ||h||), as the bits of a non-negative float
+    uint32_t pad;
+};
+
 struct ProfileRec {
     int stage;
     hipEvent_t start, stop;
@@ -83,6 +93,10 @@ struct spotlight_ctx {
     char* workspace;
     int max_lds;                     // bytes of LDS one workgroup may use on this device
     int n_cus;                       // compute units of this device
+    int score_resident;              // score workgroups the device holds at once (0: not asked yet)
+    int opt[SPOTLIGHT_OPT_COUNT];    // spotlight_set_option
+    const void* big_lds_kernels[16]; // kernels whose dynamic LDS limit has been raised already
+    int n_big_lds_kernels;
     // the weights the packed copy in the workspace was made from (all null: no copy)
     const void* packed_w1;
     const void* packed_b1;
@@ -140,6 +154,7 @@ struct HashLaunch {
     uint32_t* zero;           // if set: zero[xhead * zero_words ...) is cleared by the head's first tile
     int zero_words;
     float* wnorm;             // [weight heads][L] floats of scratch for the matrix-core path, or null
+    AuditRec* audit;          // set: the matrix-core path also checks every output against the chain
     const void* pack_w1;      // packed copies of the weights (see launch_pack_weights), or null
     const void* pack_out;
 };
@@ -157,6 +172,14 @@ int launch_retrieve(spotlight_ctx* ctx, const uint32_t* codes, int64_t n_tokens,
 
 int launch_attend(spotlight_ctx* ctx, const void* q, const void* K, const void* V,
                   const int32_t* idx, int k, float scale, float* out);
+
+// Error bound of the matrix-core second hash layer per unit of ||W2[j]|| * ||h||: `hidden` roundings
+// of 2^-24 in the binary32 chain, at most 2 * hidden additions in the matrix core each taken to err
+// by at most one unit in the last place, and the residue of the hi/lo split (2^-18, taken as 2^-17).
+inline double bulk_hash_eps(int hidden) { return 1.01 * (hidden * (0x1p-24 + 1.01 * 0x1p-22) + 0x1p-17); }
+
+// Raises a kernel's dynamic LDS limit (once per kernel and context).
+int allow_dynamic_lds(spotlight_ctx* ctx, const void* kernel, size_t bytes);
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? SPOTLIGHT_OK : SPOTLIGHT_ERR_HIP; }
 

@@ -1,0 +1,9 @@
+// Instantiates the retrieval kernels for code lengths of 8, 9 words (see retrieve_kernels.h).
+#include "retrieve_kernels.h"
+
+namespace spotlight {
+namespace retrieve_detail {
+template int launch_w<8>(spotlight_ctx*, const RetrieveArgs&);
+template int launch_w<9>(spotlight_ctx*, const RetrieveArgs&);
+}  // namespace retrieve_detail
+}  // namespace spotlight

@@ -1,0 +1,8 @@
+// Instantiates the retrieval kernels for code lengths of 16 words (see retrieve_kernels.h).
+#include "retrieve_kernels.h"
+
+namespace spotlight {
+namespace retrieve_detail {
+template int launch_w<16>(spotlight_ctx*, const RetrieveArgs&);
+}  // namespace retrieve_detail
+}  // namespace spotlight

@@ -100,9 +100,19 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.spotlight_profile_enable(None, 1) == bad
     assert lib.spotlight_profile_read(None, 0, None, None) == bad
     assert lib.spotlight_set_stream(None, None) == bad
+    assert lib.spotlight_set_option(None, 0, 1) == bad
+    assert lib.spotlight_bulk_hash_audit_read(None, None, None, None, None, None) == bad
     assert lib.spotlight_destroy(None) == sp.OK
     for rc in (0, -1, -2, -3, -4, -99):
         assert lib.spotlight_strerror(rc)
+
+
+def test_library_records_the_sources_it_was_built_from():
+    """The build id inside the library is the hash of the sources in the tree (a stale library is
+    rebuilt before the tests start), and the copy read from the file equals the loaded one."""
+    from paper_2508_19740_amd import build as hip_build
+    assert sp.build_id() == hip_build.source_id() == hip_build.built_id()
+    assert not hip_build.stale()
 
 
 def test_token_budget_matches_the_paper():

@@ -1,7 +1,10 @@
 """GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
 
 The oracle cannot hash every key of the large configs in test time, so:
-  * key codes are checked bit-exactly on whole sampled heads (C2: all heads) or sampled rows (C5);
+  * key codes are checked bit-exactly on whole sampled heads (C2: all heads; C5: one whole head of
+    a million keys per code length, and sampled rows of three more);
+  * the bulk hash's matrix-core path is compared with its all-binary32 path over the WHOLE code
+    tensor (both on the device), and audited output by output inside the kernel;
   * retrieval is checked bit-exactly on EVERY head from seeded synthetic code caches (both sides
     read the same generated codes), and on the sampled heads from real hashed codes;
   * attention is checked on every head against the oracle run on the gathered rows;
@@ -10,6 +13,7 @@ The oracle cannot hash every key of the large configs in test time, so:
 Inputs come from the seeded generator only; nothing computed by the HIP path feeds the oracle.
 """
 import math
+import sys
 
 import pytest
 import torch
@@ -21,6 +25,12 @@ from gpu_common import torch_dtype
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 ATTN_TOL = 2e-3
 DEV = "cuda:0"
+
+
+def progress(msg):
+    """A line on the real stderr, flushed: the million-token tests run for minutes."""
+    sys.__stderr__.write(f"  [{msg}]\n")
+    sys.__stderr__.flush()
 
 
 class Big:
@@ -146,13 +156,53 @@ def check_attention_all_heads(big, idx_host):
     assert worst <= ATTN_TOL, worst
 
 
-def check_sampled_heads_real_chain(big, heads):
-    """Whole heads through hash -> retrieve -> attend on both sides; the GPU ran every head."""
+def check_bulk_hash_paths_agree(big, n_rows=None):
+    """The whole code tensor, twice: second hash layer on the matrix cores (certified signs, the
+    rest recomputed) and everything on the binary32 chain.  Both on the device, every word compared.
+    Then the matrix-core call again with the audit on: the kernel evaluates every output with the
+    chain as well and reports how far the matrix cores were from it, in units of the bound's scale."""
+    import paper_2508_19740_amd as sp
+    c = big.cfg
+    n = c.n_tokens if n_rows is None else n_rows
+    big.codes.zero_()
+    big.ctx.hash_keys(big.K, *big.weights, 0, n, big.codes)
+    other = torch.zeros_like(big.codes)
+    big.ctx.set_option(sp.OPT_BULK_HASH_MATRIX_CORES, 0)
+    try:
+        big.ctx.hash_keys(big.K, *big.weights, 0, n, other)
+    finally:
+        big.ctx.set_option(sp.OPT_BULK_HASH_MATRIX_CORES, 1)
+    assert torch.equal(big.codes, other)
+    other.zero_()
+    big.ctx.set_option(sp.OPT_BULK_HASH_AUDIT, 1)
+    try:
+        big.ctx.hash_keys(big.K, *big.weights, 0, n, other)
+    finally:
+        big.ctx.set_option(sp.OPT_BULK_HASH_AUDIT, 0)
+    au = big.ctx.bulk_hash_audit_read()
+    assert torch.equal(big.codes, other)
+    del other
+    progress(f"[bulk hash audit] {c.name}: outputs {au['outputs']}, recomputed {au['listed']} "
+          f"({au['listed'] / au['outputs']:.3e}), largest |y_mfma - y_chain| / (|W2[j]| |h|) = {au['max_ratio']:.3e} "
+          f"against eps = {au['eps']:.3e} (slack x{au['eps'] / max(au['max_ratio'], 1e-30):.1f})")
+    assert au["outputs"] == c.batch * c.n_kv_heads * n * c.code_bits      # the matrix-core path did run
+    assert au["wrong"] == 0
+    assert au["max_ratio"] < au["eps"]
+    assert au["listed"] < au["outputs"] // 100
+
+
+def check_sampled_heads_real_chain(big, heads, distances=False, rehash=True):
+    """Whole heads through hash -> retrieve -> attend on both sides; the GPU ran every head.
+    With distances=True every distance of the sampled heads is compared as well."""
     c = big.cfg
     G = c.group
-    big.codes.zero_()
-    big.ctx.hash_keys(big.K, *big.weights, 0, c.n_tokens, big.codes)
-    idx = big.ctx.retrieve_topk(big.q, *big.weights, big.codes, c.n_tokens, c.topk)
+    if rehash:
+        big.codes.zero_()
+        big.ctx.hash_keys(big.K, *big.weights, 0, c.n_tokens, big.codes)
+    dist_dev = None
+    if distances:
+        dist_dev = torch.empty(c.batch, c.n_q_heads, c.n_tokens, dtype=torch.int16, device=DEV)
+    idx = big.ctx.retrieve_topk(big.q, *big.weights, big.codes, c.n_tokens, c.topk, out_dist=dist_dev)
     out = big.ctx.sparse_decode(big.q, big.K, big.V, idx, big.scale).cpu()
     idx_h = idx.cpu()
     check_index_properties(idx_h, c, big.w.needle_pos)
@@ -165,6 +215,8 @@ def check_sampled_heads_real_chain(big, heads):
             hq = hk * G + g
             _, qc = oracle.hash_rows(big.w.q[b, hq:hq + 1].contiguous(), *big.head_weights(hk), c.code_bits)
             dist = oracle.hamming(qc[0].contiguous(), want_codes)
+            if distances:
+                assert torch.equal(dist_dev[b, hq].cpu(), dist), (b, hq)
             want_idx = oracle.topk(dist, c.topk)
             assert torch.equal(idx_h[b, hq], want_idx), (b, hq)
             want = oracle.sparse_attention(big.w.q[b, hq].contiguous(), hK, hV, want_idx, big.scale)
@@ -185,7 +237,8 @@ def test_c2_every_head_against_the_full_oracle():
 def test_c3_512k_tokens():
     big = Big(wl.CONFIGS["C3"])
     try:
-        idx = check_sampled_heads_real_chain(big, [(0, 5), (0, 31)])
+        check_bulk_hash_paths_agree(big)
+        idx = check_sampled_heads_real_chain(big, [(0, 5), (0, 31)], distances=True, rehash=False)
         check_attention_all_heads(big, idx)
         check_retrieval_on_synthetic_codes(big)
         big.ctx.prepack_weights(*big.weights)      # as bench.py runs the step
@@ -197,7 +250,8 @@ def test_c3_512k_tokens():
 def test_c4_gqa_batch16():
     big = Big(wl.CONFIGS["C4"])
     try:
-        idx = check_sampled_heads_real_chain(big, [(0, 0), (9, 3), (15, 7)])
+        check_bulk_hash_paths_agree(big)
+        idx = check_sampled_heads_real_chain(big, [(0, 0), (9, 3), (15, 7)], rehash=False)
         check_attention_all_heads(big, idx)
         check_retrieval_on_synthetic_codes(big)
         big.ctx.prepack_weights(*big.weights)      # as bench.py runs the step
@@ -251,32 +305,82 @@ def c5_kv():
     return w.materialize("K", DEV), w.materialize("V", DEV)
 
 
+C5_WHOLE_HEAD = {"C5-128": (2, 17), "C5-512": (1, 9)}
+
+
 @pytest.mark.parametrize("name", ["C5-128", "C5-512"])
 def test_c5_one_million_tokens_with_growth(c5_kv, name):
+    """Config C5 as the other configs are checked, plus its cache growth: one whole (batch, head)
+    of a million keys goes hash -> retrieve -> attend on both sides; then the config's 64 decode
+    steps run through spotlight_decode_step, each appending one key per head; every appended code
+    of every head is compared with the oracle's, and on the whole head the index arrays and the
+    attention output are compared after steps 1, 32 and 64."""
     big = Big(wl.CONFIGS[name], need_kv=False)
     big.K, big.V = c5_kv
     try:
         c = big.cfg
-        N = c.n_tokens
-        # bulk build, then three decode-step appends
-        big.ctx.hash_keys(big.K, *big.weights, 0, N, big.codes)
-        big.ctx.prepack_weights(*big.weights)      # the appends and the query hash read the packed copy, as in bench.py
-        for j in range(3):
-            big.ctx.hash_keys(big.K, *big.weights, N + j, 1, big.codes)
-        # sampled rows of sampled heads, including both ends, a tile boundary and the appended keys
+        N, k, steps = c.n_tokens, c.topk, c.extra_tokens
+        assert steps == 64
+        # bulk build on the matrix cores; for the long codes (hidden 1024, four code words per
+        # wavefront) also against the all-binary32 path over the whole tensor, and audited
+        progress(f"{name}: bulk hash")
+        if name == "C5-512":
+            check_bulk_hash_paths_agree(big, n_rows=N)
+        else:
+            big.ctx.hash_keys(big.K, *big.weights, 0, N, big.codes)
+        assert int(big.codes[:, :, N:].abs().max()) == 0              # rows never hashed stay untouched
+        # sampled rows of sampled heads, including both ends and a tile boundary
         gen = torch.Generator().manual_seed(7)
-        rows = torch.cat([torch.arange(0, 40), torch.arange(N // 2 - 20, N // 2 + 20), torch.arange(N - 40, N + 3),
+        rows = torch.cat([torch.arange(0, 40), torch.arange(N // 2 - 20, N // 2 + 20), torch.arange(N - 40, N),
                           torch.randint(0, N, (400,), generator=gen)]).unique()
         for (b, hk) in [(0, 0), (2, 17), (3, 31)]:
             x = big.K[b, hk].index_select(0, rows.to(DEV)).cpu()
             _, want = oracle.hash_rows(x, *big.head_weights(hk), c.code_bits)
             got = big.codes[b, hk].index_select(0, rows.to(DEV)).cpu()
             assert torch.equal(got, want), (b, hk)
-        assert int(big.codes[:, :, N + 3:].abs().max()) == 0          # rows never hashed stay untouched
-        # the real chain over the grown cache: properties on every head
-        idx = big.ctx.retrieve_topk(big.q, *big.weights, big.codes, N + 3, c.topk).cpu()
-        check_index_properties(idx, c.scaled(n_tokens=N + 3), big.w.needle_pos)
-        check_attention_all_heads(big, idx)
+        # one whole head: all N + 64 codes by the oracle (the last 64 are the keys the steps append)
+        wb, wh = C5_WHOLE_HEAD[name]
+        progress(f"{name}: the oracle hashes head {(wb, wh)}")
+        hK = big.K[wb, wh].cpu()
+        hV = big.V[wb, wh].cpu()
+        _, head_codes = oracle.hash_rows(hK, *big.head_weights(wh), c.code_bits)
+        assert torch.equal(big.codes[wb, wh, :N].cpu(), head_codes[:N]), (wb, wh)
+        _, qc = oracle.hash_rows(big.w.q[wb, wh:wh + 1].contiguous(), *big.head_weights(wh), c.code_bits)
+
+        def check_whole_head(n, idx, out, what):
+            dist = oracle.hamming(qc[0].contiguous(), head_codes[:n].contiguous())
+            want_idx = oracle.topk(dist, k)
+            assert torch.equal(idx[wb, wh].cpu(), want_idx), (what, n)
+            want = oracle.sparse_attention(big.w.q[wb, wh].contiguous(), hK[:n], hV[:n], want_idx, big.scale)
+            assert float((out[wb, wh].cpu() - want).abs().max()) <= ATTN_TOL, (what, n)
+            return want_idx
+
+        progress(f"{name}: retrieval and attention on that head, then {steps} steps")
+        # before any growth: the three calls over the N cached tokens
+        idx = big.ctx.retrieve_topk(big.q, *big.weights, big.codes, N, k)
+        out = big.ctx.sparse_decode(big.q, big.K, big.V, idx, big.scale)
+        check_whole_head(N, idx, out, "three calls")
+        # the 64 steps: the appends and the query hash read the packed copy of the weights, as in bench.py
+        big.ctx.prepack_weights(*big.weights)
+        for j in range(steps):
+            n = N + j + 1
+            idx, out = big.ctx.decode_step(big.q, big.K, big.V, *big.weights, big.codes, n, k)
+            if j + 1 in (1, 32, 64):
+                check_whole_head(n, idx, out, "decode_step")
+                # the same step as three calls over the same grown cache
+                idx3 = big.ctx.retrieve_topk(big.q, *big.weights, big.codes, n, k)
+                assert torch.equal(idx3, idx), j
+        progress(f"{name}: appended codes, attention on every head, generated codes")
+        # every appended code of every head
+        for b in range(c.batch):
+            for hk in range(c.n_kv_heads):
+                x = big.K[b, hk, N:N + steps].cpu()
+                _, want = oracle.hash_rows(x, *big.head_weights(hk), c.code_bits)
+                assert torch.equal(big.codes[b, hk, N:N + steps].cpu(), want), (b, hk)
+        # the grown cache: properties on every head, attention on every head
+        idx_h = idx.cpu()
+        check_index_properties(idx_h, c.scaled(n_tokens=N + steps), big.w.needle_pos)
+        check_attention_all_heads(big, idx_h)
         # exact retrieval on every head from generated codes, over a ragged token count
         check_retrieval_on_synthetic_codes(big, n_tokens=N + 3)
     finally:

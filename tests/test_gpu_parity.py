@@ -208,7 +208,7 @@ def test_bulk_hash_on_matrix_cores_equals_the_binary32_kernel_and_the_oracle():
     """Bulk hashing runs its second layer on the matrix cores and recomputes outputs too close to
     zero with the defined binary32 chain.  Rows built to stress that: zeros (every output exactly
     0: the whole tile goes to the recomputation), tiny and huge magnitudes, a NaN and an infinity."""
-    import os
+    import paper_2508_19740_amd as sp
     cfg = C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=40000 + 19, topk=64, needles=0)
     c = Case(cfg)
     try:
@@ -223,13 +223,23 @@ def test_bulk_hash_on_matrix_cores_equals_the_binary32_kernel_and_the_oracle():
         c.codes.fill_(0)
         c.ctx.hash_keys(K, *c.weights, 0, n, c.codes)         # matrix-core path (bf16 weights, hidden 256)
         got = c.codes.clone()
-        os.environ["SPOTLIGHT_NO_MFMA"] = "1"
+        c.ctx.set_option(sp.OPT_BULK_HASH_MATRIX_CORES, 0)
         try:
             c.codes.fill_(0)
             c.ctx.hash_keys(K, *c.weights, 0, n, c.codes)     # all-binary32 kernel
         finally:
-            del os.environ["SPOTLIGHT_NO_MFMA"]
+            c.ctx.set_option(sp.OPT_BULK_HASH_MATRIX_CORES, 1)
         assert torch.equal(got, c.codes)
+        # the same call audited: every output also evaluated with the chain, inside the kernel
+        c.ctx.set_option(sp.OPT_BULK_HASH_AUDIT, 1)
+        c.codes.fill_(0)
+        c.ctx.hash_keys(K, *c.weights, 0, n, c.codes)
+        c.ctx.set_option(sp.OPT_BULK_HASH_AUDIT, 0)
+        au = c.ctx.bulk_hash_audit_read()
+        assert torch.equal(got, c.codes)
+        assert au["outputs"] == 2 * n * cfg.code_bits and au["wrong"] == 0
+        assert 0 < au["listed"] < au["outputs"] // 50
+        assert 0.0 < au["max_ratio"] < au["eps"]
         want = c.oracle_codes(0, 6000)                        # the stressed rows and their surroundings
         assert torch.equal(got.cpu()[:, :, :6000], want[:, :, :6000])
         # a second layer of zeros for head 0: every output is exactly 0, no sign can be certified, every
