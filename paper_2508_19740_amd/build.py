@@ -101,6 +101,32 @@ def build(verbose: bool = False, force: bool = True) -> str:
     return LIB
 
 
+def build_host_sanitized(out: str) -> str:
+    """The library with its HOST code (argument checks, planning, launch logic) compiled with
+    AddressSanitizer and UndefinedBehaviorSanitizer, the kernels left alone: for running the
+    host-only ABI tests under them.  Returns the sanitizer runtime that has to be preloaded into
+    the process that loads the library."""
+    import concurrent.futures
+    import glob
+    import tempfile
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=all"]
+    with tempfile.TemporaryDirectory(prefix="spotlight_san_") as tmp:
+        def one(src):
+            obj = os.path.join(tmp, os.path.basename(src) + ".o")
+            subprocess.run([hipcc, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fPIC", "-ffp-contract=off",
+                            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", *san, f'-DSPOTLIGHT_BUILD_ID_STRING="{ID_MARK}{source_id()}"',
+                            "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", src, "-o", obj], check=True)
+            return obj
+        with concurrent.futures.ThreadPoolExecutor(max_workers=8) as pool:
+            objs = list(pool.map(one, sources()))
+        subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address,undefined", "-fno-gpu-sanitize",
+                        "-shared-libsan", "-o", out, *objs], check=True)
+    rt = glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so")
+    return rt[0] if rt else ""
+
+
 if __name__ == "__main__":
     import sys
     print(build(verbose=True, force="--incremental" not in sys.argv))
