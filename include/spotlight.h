@@ -43,7 +43,8 @@ enum {
     SPOTLIGHT_ERR_INVALID_ARG = -1, /* null pointer, size out of range, inconsistent shapes  */
     SPOTLIGHT_ERR_UNSUPPORTED = -2, /* a well-formed request outside what the kernels cover  */
     SPOTLIGHT_ERR_WORKSPACE = -3,   /* workspace allocation failed                           */
-    SPOTLIGHT_ERR_HIP = -4          /* a HIP runtime call or kernel launch reported an error */
+    SPOTLIGHT_ERR_HIP = -4,         /* a HIP runtime call or kernel launch reported an error */
+    SPOTLIGHT_ERR_TOO_LARGE = -5    /* spotlight_decode_step_noalloc: the shape needs more scratch than the fixed buffer holds */
 };
 
 /* Kernel stages, for spotlight_profile_read. */
@@ -229,6 +230,30 @@ int spotlight_decode_step(spotlight_ctx *ctx, const void *q, const void *K, cons
                           const spotlight_hash_weights *w, uint32_t *codes, int64_t n_tokens,
                           int32_t k, int32_t n_sink, int32_t n_local, float scale,
                           int32_t *out_idx, float *out);
+
+/*
+ * spotlight_decode_step for callers that cannot allocate device memory or create a context: code
+ * under HIP graph capture set-up rules, tight serving loops, harnesses that forbid hipMalloc.  It
+ * takes the configuration instead of a context and uses, in place of a context's workspace, a
+ * fixed buffer of SPOTLIGHT_NOALLOC_SCRATCH_BYTES (32 MiB) of device memory that is part of the
+ * library's code object: every GPU the library runs on holds it until the process ends.  The call
+ * allocates and frees nothing, on the device or through any library, and does not synchronise;
+ * the five kernels are those of spotlight_decode_step and run on cfg->stream of the current device.
+ * Arguments, layouts, results and argument errors are those of spotlight_decode_step (cfg->max_topk
+ * bounds k as it does for a context); the hash weights are read as stored (no packed copy).
+ *
+ * Limit: the workspace of the shape (spotlight_workspace_bytes without the room for the packed
+ * weights: about 1 KiB per (query head, block of 4096 tokens of max_tokens) x 4 + 516 B per
+ * (query head, 32 of max_topk)) must fit the buffer, else SPOTLIGHT_ERR_TOO_LARGE and nothing is
+ * launched.  Batch 1, 32 heads, 524288 tokens, top-k 10486 needs 24.4 MB and fits.
+ * All calls on one GPU share the one buffer: calls that overlap in time on the same GPU (two
+ * streams, two threads) race; calls in stream order are safe, each clears what it needs cleared.
+ */
+#define SPOTLIGHT_NOALLOC_SCRATCH_BYTES (32u << 20)
+int spotlight_decode_step_noalloc(const spotlight_config *cfg, const void *q, const void *K, const void *V,
+                                  const spotlight_hash_weights *w, uint32_t *codes, int64_t n_tokens,
+                                  int32_t k, int32_t n_sink, int32_t n_local, float scale,
+                                  int32_t *out_idx, float *out);
 
 /*
  * Stage timing for benchmarks.  While enabled, every kernel launch carries two HIP events that are

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     Spotlight, SpotlightError, Config, HashWeights, make_config, validate_config, workspace_bytes,
     spotlight_hash_keys, spotlight_retrieve_topk, spotlight_sparse_decode, spotlight_decode_step,
     spotlight_prepack_weights, lib, SYMBOLS,
+    spotlight_decode_step_noalloc, NOALLOC_SCRATCH_BYTES, ERR_TOO_LARGE,
     build_id, OPT_BULK_HASH_MATRIX_CORES, OPT_BULK_HASH_AUDIT,
     STAGES, OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, F32, BF16,
 )

@@ -15,7 +15,8 @@ import torch
 from . import build as _build
 
 F32, BF16 = 0, 1
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5
+NOALLOC_SCRATCH_BYTES = 32 << 20
 STAGES = ("hash_keys", "hash_query", "score", "select", "attend", "merge")
 
 # every symbol include/spotlight.h declares
@@ -24,6 +25,7 @@ SYMBOLS = (
     "spotlight_set_stream", "spotlight_strerror", "spotlight_hash_keys", "spotlight_retrieve_topk",
     "spotlight_sparse_decode", "spotlight_decode_step", "spotlight_prepack_weights", "spotlight_profile_enable",
     "spotlight_profile_read", "spotlight_build_id", "spotlight_set_option", "spotlight_bulk_hash_audit_read",
+    "spotlight_decode_step_noalloc",
 )
 OPT_BULK_HASH_MATRIX_CORES, OPT_BULK_HASH_AUDIT = 0, 1
 
@@ -61,6 +63,8 @@ def _load() -> C.CDLL:
     lib.spotlight_sparse_decode.argtypes = [vp, vp, vp, vp, vp, i32, C.c_float, vp]
     lib.spotlight_decode_step.argtypes = [vp, vp, vp, vp, C.POINTER(HashWeights), vp, i64, i32, i32, i32,
                                           C.c_float, vp, vp]
+    lib.spotlight_decode_step_noalloc.argtypes = [C.POINTER(Config), vp, vp, vp, C.POINTER(HashWeights), vp, i64, i32,
+                                                  i32, i32, C.c_float, vp, vp]
     lib.spotlight_prepack_weights.argtypes = [vp, C.POINTER(HashWeights)]
     lib.spotlight_profile_enable.argtypes = [vp, C.c_int]
     lib.spotlight_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -277,6 +281,18 @@ class Spotlight:
                 raise SpotlightError(rc, "spotlight_profile_read")
             out[name] = (ms.value, n.value)
         return out
+
+
+def spotlight_decode_step_noalloc(cfg: Config, q, K, V, w1, b1, w2, codes, n_tokens: int, k: int, n_sink: int,
+                                  n_local: int, scale: float, out_idx, out) -> int:
+    """The decode step without a context: the library's fixed scratch buffer is the workspace and
+    nothing is allocated, here or in the library, so the caller brings out_idx and out.  Pointers
+    only: the tensors must be contiguous device tensors of the shapes spotlight_decode_step takes.
+    Returns the C return code."""
+    w = HashWeights(w1.data_ptr(), None if b1 is None else b1.data_ptr(), None if w2 is None else w2.data_ptr())
+    return lib.spotlight_decode_step_noalloc(C.byref(cfg), q.data_ptr(), K.data_ptr(), V.data_ptr(), C.byref(w),
+                                             codes.data_ptr(), n_tokens, k, n_sink, n_local, float(scale),
+                                             out_idx.data_ptr(), out.data_ptr())
 
 
 # flat functions named like the C entry points

@@ -127,6 +127,7 @@ const char* spotlight_strerror(int rc)
     case SPOTLIGHT_ERR_UNSUPPORTED: return "unsupported configuration";
     case SPOTLIGHT_ERR_WORKSPACE: return "workspace allocation failed";
     case SPOTLIGHT_ERR_HIP: return "HIP runtime error";
+    case SPOTLIGHT_ERR_TOO_LARGE: return "problem too large for the static scratch buffer";
     default: return "unknown error";
     }
 }
@@ -353,13 +354,18 @@ int spotlight_retrieve_topk(spotlight_ctx* ctx, const void* q, const spotlight_h
     return launch_retrieve(ctx, codes, n_tokens, k, 0, 0, out_idx, out_dist);
 }
 
-int spotlight_decode_step(spotlight_ctx* ctx, const void* q, const void* K, const void* V,
-                          const spotlight_hash_weights* w, uint32_t* codes, int64_t n_tokens, int32_t k,
-                          int32_t n_sink, int32_t n_local, float scale, int32_t* out_idx, float* out)
+}  // extern "C"
+
+namespace spotlight {
+
+// Host-only argument checks of the decode step.
+int check_step_args(const spotlight_ctx* ctx, const void* q, const void* K, const void* V, const spotlight_hash_weights* w,
+                    const uint32_t* codes, int64_t n_tokens, int32_t k, int32_t n_sink, int32_t n_local,
+                    const int32_t* out_idx, const float* out)
 {
     if (!ctx || !q || !K || !V || !codes || !out_idx || !out) return SPOTLIGHT_ERR_INVALID_ARG;
     const Plan& p = ctx->plan;
-    int rc = check_weights(ctx, w);
+    const int rc = check_weights(ctx, w);
     if (rc != SPOTLIGHT_OK) return rc;
     if (n_tokens < 1 || n_tokens > p.Nmax) return SPOTLIGHT_ERR_INVALID_ARG;
     if (k < 1 || k > n_tokens || k > p.max_topk) return SPOTLIGHT_ERR_INVALID_ARG;
@@ -367,13 +373,33 @@ int spotlight_decode_step(spotlight_ctx* ctx, const void* q, const void* K, cons
     const int64_t n_forced = static_cast<int64_t>(n_sink) + n_local >= n_tokens ? n_tokens : static_cast<int64_t>(n_sink) + n_local;
     if (n_forced > k) return SPOTLIGHT_ERR_INVALID_ARG;
     if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(codes)) return SPOTLIGHT_ERR_INVALID_ARG;
+    return SPOTLIGHT_OK;
+}
 
+// The decode step of spotlight_decode_step and spotlight_decode_step_noalloc: argument checks, then five launches.
+int decode_step(spotlight_ctx* ctx, const void* q, const void* K, const void* V, const spotlight_hash_weights* w,
+                uint32_t* codes, int64_t n_tokens, int32_t k, int32_t n_sink, int32_t n_local, float scale,
+                int32_t* out_idx, float* out)
+{
+    int rc = check_step_args(ctx, q, K, V, w, codes, n_tokens, k, n_sink, n_local, out_idx, out);
+    if (rc != SPOTLIGHT_OK) return rc;
     // queries first: their workgroups also clear the histograms
     rc = launch_hash_pair(ctx, query_job(ctx, q, w), key_job(ctx, K, w, n_tokens - 1, 1, codes), SPOTLIGHT_STAGE_HASH_QUERY);
     if (rc != SPOTLIGHT_OK) return rc;
     rc = launch_retrieve(ctx, codes, n_tokens, k, n_sink, n_local, out_idx, nullptr);
     if (rc != SPOTLIGHT_OK) return rc;
     return launch_attend(ctx, q, K, V, out_idx, k, scale, out);
+}
+
+}  // namespace spotlight
+
+extern "C" {
+
+int spotlight_decode_step(spotlight_ctx* ctx, const void* q, const void* K, const void* V,
+                          const spotlight_hash_weights* w, uint32_t* codes, int64_t n_tokens, int32_t k,
+                          int32_t n_sink, int32_t n_local, float scale, int32_t* out_idx, float* out)
+{
+    return decode_step(ctx, q, K, V, w, codes, n_tokens, k, n_sink, n_local, scale, out_idx, out);
 }
 
 int spotlight_sparse_decode(spotlight_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* idx,

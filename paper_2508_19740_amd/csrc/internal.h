@@ -181,6 +181,15 @@ inline double bulk_hash_eps(int hidden) { return 1.01 * (hidden * (0x1p-24 + 1.0
 // Raises a kernel's dynamic LDS limit (once per kernel and context).
 int allow_dynamic_lds(spotlight_ctx* ctx, const void* kernel, size_t bytes);
 
+// Host-only argument checks of the decode step (SPOTLIGHT_OK or the error spotlight_decode_step returns).
+int check_step_args(const spotlight_ctx* ctx, const void* q, const void* K, const void* V, const spotlight_hash_weights* w,
+                    const uint32_t* codes, int64_t n_tokens, int32_t k, int32_t n_sink, int32_t n_local,
+                    const int32_t* out_idx, const float* out);
+// spotlight_decode_step on any context, also one that lives on the caller's stack.
+int decode_step(spotlight_ctx* ctx, const void* q, const void* K, const void* V, const spotlight_hash_weights* w,
+                uint32_t* codes, int64_t n_tokens, int32_t k, int32_t n_sink, int32_t n_local, float scale,
+                int32_t* out_idx, float* out);
+
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? SPOTLIGHT_OK : SPOTLIGHT_ERR_HIP; }
 
 }  // namespace spotlight

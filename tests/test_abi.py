@@ -101,9 +101,10 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.spotlight_profile_read(None, 0, None, None) == bad
     assert lib.spotlight_set_stream(None, None) == bad
     assert lib.spotlight_set_option(None, 0, 1) == bad
+    assert lib.spotlight_decode_step_noalloc(None, None, None, None, None, None, 1, 1, 0, 0, 0.1, None, None) == bad
     assert lib.spotlight_bulk_hash_audit_read(None, None, None, None, None, None) == bad
     assert lib.spotlight_destroy(None) == sp.OK
-    for rc in (0, -1, -2, -3, -4, -99):
+    for rc in (0, -1, -2, -3, -4, -5, -99):
         assert lib.spotlight_strerror(rc)
 
 
