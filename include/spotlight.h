@@ -55,7 +55,8 @@ enum {
     SPOTLIGHT_STAGE_SELECT = 3,     /* threshold, offsets, ordered output of the selected tokens */
     SPOTLIGHT_STAGE_ATTEND = 4,     /* gather + softmax attention over a split of the rows       */
     SPOTLIGHT_STAGE_MERGE = 5,      /* merge of the splits' partial results                      */
-    SPOTLIGHT_STAGE_COUNT = 6
+    SPOTLIGHT_STAGE_STEP_SMALL = 6, /* the whole decode step of a short context, as one kernel   */
+    SPOTLIGHT_STAGE_COUNT = 7
 };
 
 /* Switches of a context, for spotlight_set_option. */
@@ -67,7 +68,11 @@ enum {
     /* 1: the matrix-core bulk hash also evaluates EVERY output with the chain and records how far
      * the two results are apart (spotlight_bulk_hash_audit_read).  Slow; for tests.  Default 0. */
     SPOTLIGHT_OPT_BULK_HASH_AUDIT = 1,
-    SPOTLIGHT_OPT_COUNT = 2
+    /* 1 (default): spotlight_decode_step runs a short context (at most 65536 tokens, codes of at most
+     * 256 bits, at most 32 MB of codes in all) as ONE kernel launch, a workgroup per (batch,
+     * key-value head); 0: always the five launches of the general path.  Same codes and indices. */
+    SPOTLIGHT_OPT_STEP_SINGLE_LAUNCH = 2,
+    SPOTLIGHT_OPT_COUNT = 3
 };
 
 typedef struct {
@@ -221,8 +226,9 @@ int spotlight_sparse_decode(spotlight_ctx *ctx, const void *q, const void *K, co
  *   codes    [B, Hkv, Nmax, W]  uint32     row n_tokens-1 is written, rows 0 .. n_tokens-1 are read
  *   out_idx  [B, Hq, k]         int32      selected token indices in increasing order
  *   out      [B, Hq, d]         float32
- * The call enqueues five kernels on the context's stream and nothing else (no allocation, no
- * memset, no copy), so it can be captured into a HIP graph.
+ * The call enqueues five kernels on the context's stream (one kernel for a short context, see
+ * SPOTLIGHT_OPT_STEP_SINGLE_LAUNCH) and nothing else (no allocation, no memset, no copy), so it can
+ * be captured into a HIP graph.
  * Errors: INVALID_ARG unless 1 <= n_tokens <= Nmax, 1 <= k <= min(n_tokens, max_topk),
  * n_sink >= 0, n_local >= 0 and the number of forced tokens is at most k.
  */

@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     spotlight_hash_keys, spotlight_retrieve_topk, spotlight_sparse_decode, spotlight_decode_step,
     spotlight_prepack_weights, lib, SYMBOLS,
     spotlight_decode_step_noalloc, NOALLOC_SCRATCH_BYTES, ERR_TOO_LARGE,
-    build_id, OPT_BULK_HASH_MATRIX_CORES, OPT_BULK_HASH_AUDIT,
+    build_id, OPT_BULK_HASH_MATRIX_CORES, OPT_BULK_HASH_AUDIT, OPT_STEP_SINGLE_LAUNCH,
     STAGES, OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, F32, BF16,
 )
 from .policy import token_budget  # noqa: F401,E402

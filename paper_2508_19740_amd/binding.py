@@ -17,7 +17,7 @@ from . import build as _build
 F32, BF16 = 0, 1
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5
 NOALLOC_SCRATCH_BYTES = 32 << 20
-STAGES = ("hash_keys", "hash_query", "score", "select", "attend", "merge")
+STAGES = ("hash_keys", "hash_query", "score", "select", "attend", "merge", "step_small")
 
 # every symbol include/spotlight.h declares
 SYMBOLS = (
@@ -27,7 +27,7 @@ SYMBOLS = (
     "spotlight_profile_read", "spotlight_build_id", "spotlight_set_option", "spotlight_bulk_hash_audit_read",
     "spotlight_decode_step_noalloc",
 )
-OPT_BULK_HASH_MATRIX_CORES, OPT_BULK_HASH_AUDIT = 0, 1
+OPT_BULK_HASH_MATRIX_CORES, OPT_BULK_HASH_AUDIT, OPT_STEP_SINGLE_LAUNCH = 0, 1, 2
 
 
 class Config(C.Structure):

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.environ.get("SPOTLIGHT_LIB") or os.path.join(HERE, "libspotlight.so")
 OBJDIR = os.path.join(HERE, "_build")          # object files of the last build (not tracked)
-HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "retrieve_kernels.h"),
+HEADERS = [os.path.join(CSRC, h) for h in sorted(os.listdir(CSRC)) if h.endswith(".h")] + [
            os.path.join(ROOT, "include", "spotlight.h")]
 ID_MARK = "SPOTLIGHT_BUILD_ID="
 

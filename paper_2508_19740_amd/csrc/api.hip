@@ -157,6 +157,7 @@ int spotlight_create(spotlight_ctx** out, const spotlight_config* cfg)
     ctx->max_lds = lds;
     ctx->n_cus = cus;
     ctx->opt[SPOTLIGHT_OPT_BULK_HASH_MATRIX_CORES] = 1;
+    ctx->opt[SPOTLIGHT_OPT_STEP_SINGLE_LAUNCH] = 1;
     void* ws = nullptr;
     if (hipMalloc(&ws, plan.total_bytes) != hipSuccess) {
         (void)hipGetLastError();
@@ -383,6 +384,9 @@ int decode_step(spotlight_ctx* ctx, const void* q, const void* K, const void* V,
 {
     int rc = check_step_args(ctx, q, K, V, w, codes, n_tokens, k, n_sink, n_local, out_idx, out);
     if (rc != SPOTLIGHT_OK) return rc;
+    if (step_small_applies(ctx, n_tokens))   // a short context: the whole step is one kernel
+        return launch_step_small(ctx, query_job(ctx, q, w), key_job(ctx, K, w, n_tokens - 1, 1, codes), q, K, V, codes,
+                                 n_tokens, k, n_sink, n_local, scale, out_idx, out);
     // queries first: their workgroups also clear the histograms
     rc = launch_hash_pair(ctx, query_job(ctx, q, w), key_job(ctx, K, w, n_tokens - 1, 1, codes), SPOTLIGHT_STAGE_HASH_QUERY);
     if (rc != SPOTLIGHT_OK) return rc;

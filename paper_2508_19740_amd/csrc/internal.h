@@ -181,6 +181,13 @@ inline double bulk_hash_eps(int hidden) { return 1.01 * (hidden * (0x1p-24 + 1.0
 // Raises a kernel's dynamic LDS limit (once per kernel and context).
 int allow_dynamic_lds(spotlight_ctx* ctx, const void* kernel, size_t bytes);
 
+// The decode step of a short context as one kernel (step_small.hip): whether it serves this call,
+// and its launch with the two hash jobs of the step.
+bool step_small_applies(const spotlight_ctx* ctx, int64_t n_tokens);
+int launch_step_small(spotlight_ctx* ctx, const HashLaunch& qjob, const HashLaunch& kjob, const void* q, const void* K,
+                      const void* V, const uint32_t* codes, int64_t n_tokens, int k, int n_sink, int n_local,
+                      float scale, int32_t* out_idx, float* out);
+
 // Host-only argument checks of the decode step (SPOTLIGHT_OK or the error spotlight_decode_step returns).
 int check_step_args(const spotlight_ctx* ctx, const void* q, const void* K, const void* V, const spotlight_hash_weights* w,
                     const uint32_t* codes, int64_t n_tokens, int32_t k, int32_t n_sink, int32_t n_local,

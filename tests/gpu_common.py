@@ -48,5 +48,19 @@ class Case:
         oracle.hash_keys(self.hK, *self.hweights, cfg.code_bits, t0, n, codes)
         return codes
 
+    def step_path(self, one_launch: bool):
+        """Which way spotlight_decode_step runs a short context: one kernel, or the five of the general path."""
+        import paper_2508_19740_amd as sp
+        self.ctx.set_option(sp.OPT_STEP_SINGLE_LAUNCH, 1 if one_launch else 0)
+
+    def launches_of(self, fn):
+        """Kernel launches per stage that fn() makes on this context."""
+        self.ctx.profile_enable(True)
+        try:
+            fn()
+            return {name: n for name, (_, n) in self.ctx.profile_read().items()}
+        finally:
+            self.ctx.profile_enable(False)
+
     def close(self):
         self.ctx.close()

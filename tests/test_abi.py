@@ -32,7 +32,7 @@ def test_header_symbols_are_exported_and_bound():
 
 
 def test_header_compiles_as_plain_c():
-    src = '#include "spotlight.h"\nint main(void){ spotlight_config c; (void)c; return SPOTLIGHT_STAGE_COUNT == 6 ? 0 : 1; }\n'
+    src = '#include "spotlight.h"\nint main(void){ spotlight_config c; (void)c; return SPOTLIGHT_STAGE_COUNT == 7 ? 0 : 1; }\n'
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-fsyntax-only", "-I", os.path.join(ROOT, "include"),
                     "-x", "c", "-"], input=src, text=True, check=True)
 

@@ -26,14 +26,20 @@ def test_decode_step_for_every_code_length_and_group_size(words, group):
     c = Case(cfg)
     try:
         base = c.oracle_codes(0, n - 1)
-        for n_sink, n_local, k in ((0, 0, cfg.topk), (4, 64, cfg.topk), (0, 1, 1), (3, 0, n // 2)):
-            want_codes = base.clone()
-            want_idx, want_out = oracle.decode_step(c.w.q, c.hK, c.hV, *c.hweights, want_codes, n, k,
-                                                    n_sink, n_local, c.scale)
-            c.codes.copy_(base)
-            idx, out = c.ctx.decode_step(c.q, c.K, c.V, *c.weights, c.codes, n, k, n_sink, n_local)
-            assert torch.equal(c.codes.cpu(), want_codes), (n_sink, n_local, k)
-            assert torch.equal(idx.cpu(), want_idx), (n_sink, n_local, k)
-            assert float((out.cpu() - want_out).abs().max()) <= ATTN_TOL, (n_sink, n_local, k)
+        # the general path (its kernels are what this test instantiates), then, for codes of at most
+        # 256 bits, the same step as one kernel launch
+        for one_launch in ((False, True) if words <= 8 else (False,)):
+            c.step_path(one_launch)
+            for n_sink, n_local, k in ((0, 0, cfg.topk), (4, 64, cfg.topk), (0, 1, 1), (3, 0, n // 2)):
+                want_codes = base.clone()
+                want_idx, want_out = oracle.decode_step(c.w.q, c.hK, c.hV, *c.hweights, want_codes, n, k,
+                                                        n_sink, n_local, c.scale)
+                c.codes.copy_(base)
+                idx, out = c.ctx.decode_step(c.q, c.K, c.V, *c.weights, c.codes, n, k, n_sink, n_local)
+                assert torch.equal(c.codes.cpu(), want_codes), (one_launch, n_sink, n_local, k)
+                assert torch.equal(idx.cpu(), want_idx), (one_launch, n_sink, n_local, k)
+                assert float((out.cpu() - want_out).abs().max()) <= ATTN_TOL, (one_launch, n_sink, n_local, k)
+            ran = c.launches_of(lambda: c.ctx.decode_step(c.q, c.K, c.V, *c.weights, c.codes, n, cfg.topk, 0, 0))
+            assert (ran["step_small"], ran["score"]) == ((1, 0) if one_launch else (0, 1))
     finally:
         c.close()
