@@ -68,9 +68,11 @@ enum {
     /* 1: the matrix-core bulk hash also evaluates EVERY output with the chain and records how far
      * the two results are apart (spotlight_bulk_hash_audit_read).  Slow; for tests.  Default 0. */
     SPOTLIGHT_OPT_BULK_HASH_AUDIT = 1,
-    /* 1 (default): spotlight_decode_step runs a short context (at most 65536 tokens, codes of at most
-     * 256 bits, at most 32 MB of codes in all) as ONE kernel launch, a workgroup per (batch,
-     * key-value head); 0: always the five launches of the general path.  Same codes and indices. */
+    /* 1: spotlight_decode_step runs a short context (at most 65536 tokens, codes of at most 256
+     * bits, at most 32 MB of codes in all) as ONE kernel launch, a workgroup per (batch, key-value
+     * head); 0 (default): always the five launches of the general path.  Same codes and indices.
+     * Off by default because it measured slower above about 4096 tokens per head (one compute
+     * unit per head against eight or more). */
     SPOTLIGHT_OPT_STEP_SINGLE_LAUNCH = 2,
     SPOTLIGHT_OPT_COUNT = 3
 };
@@ -226,7 +228,7 @@ int spotlight_sparse_decode(spotlight_ctx *ctx, const void *q, const void *K, co
  *   codes    [B, Hkv, Nmax, W]  uint32     row n_tokens-1 is written, rows 0 .. n_tokens-1 are read
  *   out_idx  [B, Hq, k]         int32      selected token indices in increasing order
  *   out      [B, Hq, d]         float32
- * The call enqueues five kernels on the context's stream (one kernel for a short context, see
+ * The call enqueues five kernels on the context's stream (one kernel for a short context under
  * SPOTLIGHT_OPT_STEP_SINGLE_LAUNCH) and nothing else (no allocation, no memset, no copy), so it can
  * be captured into a HIP graph.
  * Errors: INVALID_ARG unless 1 <= n_tokens <= Nmax, 1 <= k <= min(n_tokens, max_topk),

@@ -157,7 +157,6 @@ int spotlight_create(spotlight_ctx** out, const spotlight_config* cfg)
     ctx->max_lds = lds;
     ctx->n_cus = cus;
     ctx->opt[SPOTLIGHT_OPT_BULK_HASH_MATRIX_CORES] = 1;
-    ctx->opt[SPOTLIGHT_OPT_STEP_SINGLE_LAUNCH] = 1;
     void* ws = nullptr;
     if (hipMalloc(&ws, plan.total_bytes) != hipSuccess) {
         (void)hipGetLastError();

@@ -58,7 +58,6 @@ extern "C" int spotlight_decode_step_noalloc(const spotlight_config* cfg, const 
     // everything the step's kernels touch lies in front of the room for the packed weights
     if (ctx.plan.off_pack_w1 > sizeof(scratch)) return SPOTLIGHT_ERR_TOO_LARGE;
     ctx.cfg = *cfg;
-    ctx.opt[SPOTLIGHT_OPT_STEP_SINGLE_LAUNCH] = 0;   // this entry point is the step on the scratch buffer: the general path
     ctx.stream = static_cast<hipStream_t>(cfg->stream);
     rc = check_step_args(&ctx, q, K, V, w, codes, n_tokens, k, n_sink, n_local, out_idx, out);   // before any HIP call
     if (rc != SPOTLIGHT_OK) return rc;

@@ -20,6 +20,13 @@
 //
 // Same results as the general path: codes and index arrays bit for bit (the selection is the first
 // k tokens in (bin, token) order either way); the attention output differs in summation order only.
+//
+// Measured, it does NOT pay on this chip, which is why the path is an option that is off by default:
+// one compute unit streams about 113 GB/s, so a head of 32768 tokens x 16 bytes costs 4.6 us per pass
+// where the general path spreads it over eight compute units.  Batch 1, 32 heads, 32768 tokens,
+// top-k 656: 58 us as one launch (hash 12, count 18, bound + select 19, attend 10) against 27 us as
+// five; the two meet at about 4096 tokens per head (24 us) and at 1024 tokens the one launch is
+// ahead by 2 us (21.5 against 23.6).
 #pragma once
 #include <type_traits>
 

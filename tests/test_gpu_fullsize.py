@@ -230,17 +230,17 @@ def test_c2_every_head_against_the_full_oracle():
         c = big.cfg
         idx = check_sampled_heads_real_chain(big, [(0, h) for h in range(c.n_kv_heads)])
         check_attention_all_heads(big, idx)
-        # the one-call step, which runs a context of this size as ONE kernel launch (checked), and
-        # as the five launches of the general path
+        # the one-call step as the five launches of the general path, and as ONE kernel launch (an
+        # option; that it is what ran is checked)
         import paper_2508_19740_amd as sp
         big.ctx.prepack_weights(*big.weights)
+        check_decode_step_on_synthetic_codes(big)
+        big.ctx.set_option(sp.OPT_STEP_SINGLE_LAUNCH, 1)
         big.ctx.profile_enable(True)
         check_decode_step_on_synthetic_codes(big)
         ran = big.ctx.profile_read()
         big.ctx.profile_enable(False)
         assert ran["step_small"][1] == 1 and ran["score"][1] == 0
-        big.ctx.set_option(sp.OPT_STEP_SINGLE_LAUNCH, 0)
-        check_decode_step_on_synthetic_codes(big)
     finally:
         big.close()
 
