@@ -191,6 +191,10 @@ class Spotlight:
             rc = lib.spotlight_prepack_weights(self._h, C.byref(w))
         if rc != OK:
             raise SpotlightError(rc, "spotlight_prepack_weights")
+        # The library recognises the arrays its copy was made from by their addresses.  Holding the
+        # tensors here keeps those addresses from being freed and handed to other weights while the
+        # copy is in use.  (An update of the arrays IN PLACE still needs a new prepack_weights call.)
+        self._packed_from = None if w1 is None else (w1, b1, w2)
 
     def hash_keys(self, K, w1, b1, w2, t0: int, n_new: int, codes):
         self._sync_stream()
