@@ -12,7 +12,7 @@
 namespace spotlight {
 
 constexpr int kHeadDim = 128;
-constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts of 64 lanes per workgroup
+constexpr int kThreads = 256;       // 4 wavefronts of 64 lanes per workgroup (all kernels but the single-launch step)
 constexpr int kMaxGroup = 8;        // query heads per key-value head
 constexpr int kAttendMinRows = 32;  // smallest number of gathered rows one workgroup takes
 constexpr int kTokensPerBlock = 4096;  // tokens one score / select workgroup covers (16 per thread)
