@@ -17,7 +17,7 @@ bool step_small_applies(const spotlight_ctx* ctx, int64_t n_tokens)
     if (!ctx->opt[SPOTLIGHT_OPT_STEP_SINGLE_LAUNCH]) return false;
     if (n_tokens > kSmMaxTokens || p.W > 8 || p.hidden % kHeadDim != 0 || p.hidden > kSmMaxHidden) return false;
     if (static_cast<int64_t>(p.B) * p.Hkv * n_tokens * p.W * 4 > kSmMaxCodeBytes) return false;
-    return small_lds_bytes(p, small_chw(n_tokens)) <= static_cast<size_t>(ctx->max_lds);
+    return small_lds_bytes(p, n_tokens, false) <= static_cast<size_t>(ctx->max_lds);
 }
 
 int launch_step_small(spotlight_ctx* ctx, const HashLaunch& qjob, const HashLaunch& kjob, const void* q, const void* K,
@@ -47,7 +47,9 @@ int launch_step_small(spotlight_ctx* ctx, const HashLaunch& qjob, const HashLaun
     a.chw = small_chw(n_tokens);
     a.packed = qjob.pack_out && (p.hidden == 0 || qjob.pack_w1) && kjob.pack_out == qjob.pack_out && kjob.pack_w1 == qjob.pack_w1;
     a.scale = scale;
-    const size_t lds = small_lds_bytes(p, a.chw);
+    a.n_pad = small_n_pad(n_tokens);
+    a.cache_bins = small_lds_bytes(p, n_tokens, true) <= static_cast<size_t>(ctx->max_lds) ? 1 : 0;
+    const size_t lds = small_lds_bytes(p, n_tokens, a.cache_bins != 0);
     const bool kvb = p.kv_dtype == SPOTLIGHT_BF16, wb = p.w_dtype == SPOTLIGHT_BF16;
     if (kvb && wb) return launch_small<true, true>(ctx, a, lds);
     if (!kvb && wb) return launch_small<false, true>(ctx, a, lds);

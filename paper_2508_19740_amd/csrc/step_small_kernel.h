@@ -12,21 +12,22 @@
 //   count    every cached code of the head is read once, XOR + popcount against the G query codes,
 //            distances counted in an LDS histogram (bin 0: forced tokens, bin d + 1: distance d)
 //   bound    per query head, the bin T with count(bin < T) < k <= count(bin <= T), r = k - count(bin < T)
-//   select   per query head: the codes are read again (they are in the cache now), tokens with
-//            bin < T and bin == T marked in two LDS bitmaps by wave ballots, the ties trimmed to the
-//            first r in token order, the indices written in increasing order
+//   select   per query head: every token's bin comes back from an LDS copy made while counting (or,
+//            if that does not fit, the codes are read again: they are in the cache now), tokens with
+//            bin < T and bin == T are marked in two LDS bitmaps by wave ballots, the ties trimmed to
+//            the first r in token order, the indices written in increasing order
 //   attend   the selected rows gathered by the eight wavefronts (online softmax per wavefront over
 //            batches of rows, merged through LDS), output written
 //
 // Same results as the general path: codes and index arrays bit for bit (the selection is the first
 // k tokens in (bin, token) order either way); the attention output differs in summation order only.
 //
-// Measured, it does NOT pay on this chip, which is why the path is an option that is off by default:
-// one compute unit streams about 113 GB/s, so a head of 32768 tokens x 16 bytes costs 4.6 us per pass
-// where the general path spreads it over eight compute units.  Batch 1, 32 heads, 32768 tokens,
-// top-k 656: 58 us as one launch (hash 12, count 18, bound + select 19, attend 10) against 27 us as
-// five; the two meet at about 4096 tokens per head (24 us) and at 1024 tokens the one launch is
-// ahead by 2 us (21.5 against 23.6).
+// Measured, it does NOT pay on this chip beyond a few thousand tokens per head, which is why the path
+// is an option that is off by default: one compute unit streams about 113 GB/s, so a head of 32768
+// tokens x 16 bytes costs 4.6 us per pass where the general path spreads it over eight compute units.
+// Batch 1, 32 heads, top-k 2 %: 32768 tokens 46 us as one launch (dispatch 4, hash 8, count 14, bound
+// + select 9, attend 10) against 27 us as five; 16384 tokens 31 against 25; 8192 tokens 25.0 against
+// 24.1; 4096 tokens 22.3 against 23.7; 2048 tokens 21.0 against 23.8.
 #pragma once
 #include <type_traits>
 
@@ -56,6 +57,8 @@ struct SmallArgs {
     int k, Hq, Hkv, G;
     int act_dim;      // floats of hidden activations per hashing group
     int chw;          // bitmap words per thread (tokens / 16384, rounded up)
+    int n_pad;        // tokens rounded up to a multiple of the workgroup size
+    int cache_bins;   // the histogram bin of every (query head, token) is kept in LDS between the two passes
     int packed;
     float scale;
 };
@@ -104,7 +107,7 @@ __global__ __launch_bounds__(kSmThreads) void step_small_kernel(SmallArgs a)
     constexpr int BINS = L + 2;
     constexpr int CH = (BINS + 63) / 64;
     constexpr int R = kSmRep;
-    constexpr int U = 4;   // keys a thread has in flight
+    constexpr int U = 8;   // keys a thread has in flight
 
     extern __shared__ __align__(16) uint32_t lds[];
     const int G = a.G;
@@ -121,6 +124,7 @@ __global__ __launch_bounds__(kSmThreads) void step_small_kernel(SmallArgs a)
     float* s_m = reinterpret_cast<float*>(eq_bits + kSmThreads * a.chw);   // [waves]
     float* s_l = s_m + kSmWaves;                                       // [waves]
     float* s_acc = s_l + kSmWaves;                                     // [waves][128]
+    uint16_t* bin_cache = reinterpret_cast<uint16_t*>(s_acc + kSmWaves * kHeadDim);   // [G][n_pad], if cache_bins
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int grp = tid >> 8, gtid = tid & 255;
@@ -154,13 +158,10 @@ __global__ __launch_bounds__(kSmThreads) void step_small_kernel(SmallArgs a)
         for (int w = 0; w < W; ++w) d += static_cast<uint32_t>(__builtin_popcount(kw[w] ^ qcode[g * W + w]));
         return d;
     };
-    // the code of token t; the key appended by this step comes from LDS (its store to memory may still be on its way)
-    auto fix_new = [&](int t, uint32_t (&kw)[W]) {
-        if (t == n - 1) {
-#pragma unroll
-            for (int w = 0; w < W; ++w) kw[w] = newkey[w];
-        }
-    };
+    // (The code of the key appended by this step was stored to memory by this workgroup before the
+    // barrier above, so the loads below see it.)
+    const int sink_end = static_cast<int>(min(a.n_sink, a.n_tokens));          // forced: t < sink_end or t >= local_begin
+    const int local_begin = static_cast<int>(max(static_cast<int64_t>(0), a.local_begin));
     for (int t0 = tid; t0 < n; t0 += kSmThreads * U) {
         uint32_t kw[U][W];
 #pragma unroll
@@ -172,11 +173,11 @@ __global__ __launch_bounds__(kSmThreads) void step_small_kernel(SmallArgs a)
         for (int u = 0; u < U; ++u) {
             const int t = t0 + u * kSmThreads;
             if (t < n) {
-                fix_new(t, kw[u]);
-                const bool forced = t < a.n_sink || t >= a.local_begin;
+                const bool forced = t < sink_end || t >= local_begin;
                 for (int g = 0; g < G; ++g) {
                     const uint32_t bin = forced ? 0u : 1u + distance(kw[u], g);
                     atomicAdd(&hist[(g * BINS + bin) * R + rep], 1u);
+                    if (a.cache_bins) bin_cache[g * a.n_pad + t] = static_cast<uint16_t>(bin);
                 }
             }
         }
@@ -232,10 +233,12 @@ __global__ __launch_bounds__(kSmThreads) void step_small_kernel(SmallArgs a)
         // bitmaps: wavefront w of pass `it` covers tokens it * threads + 64 w ...: two words of each bitmap
         for (int it0 = 0; it0 < n_iter; it0 += U) {
             uint32_t kw[U][W];
+            if (!a.cache_bins) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int t = (it0 + u) * kSmThreads + tid;
-                if (it0 + u < n_iter && t < n) load_code<W>(hc + static_cast<int64_t>(t) * W, kw[u]);
+                for (int u = 0; u < U; ++u) {
+                    const int t = (it0 + u) * kSmThreads + tid;
+                    if (it0 + u < n_iter && t < n) load_code<W>(hc + static_cast<int64_t>(t) * W, kw[u]);
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -243,9 +246,12 @@ __global__ __launch_bounds__(kSmThreads) void step_small_kernel(SmallArgs a)
                 const int t = (it0 + u) * kSmThreads + tid;
                 uint32_t bin = 0xffffffffu;
                 if (t < n) {
-                    fix_new(t, kw[u]);
-                    const bool forced = t < a.n_sink || t >= a.local_begin;
-                    bin = forced ? 0u : 1u + distance(kw[u], g);
+                    if (a.cache_bins) {
+                        bin = bin_cache[g * a.n_pad + t];
+                    } else {
+                        const bool forced = t < sink_end || t >= local_begin;
+                        bin = forced ? 0u : 1u + distance(kw[u], g);
+                    }
                 }
                 const unsigned long long mlt = __ballot(bin < T);
                 const unsigned long long meq = __ballot(bin == T);
@@ -386,13 +392,17 @@ __global__ __launch_bounds__(kSmThreads) void step_small_kernel(SmallArgs a)
 
 inline int small_chw(int64_t n_tokens) { return static_cast<int>((n_tokens + 32 * kSmThreads - 1) / (32 * kSmThreads)); }
 
-inline size_t small_lds_bytes(const Plan& p, int chw)
+inline int small_n_pad(int64_t n_tokens) { return static_cast<int>((n_tokens + kSmThreads - 1) / kSmThreads * kSmThreads); }
+
+// LDS of one workgroup without / with the cache of every token's histogram bin.
+inline size_t small_lds_bytes(const Plan& p, int64_t n_tokens, bool cache_bins)
 {
     const int act_dim = p.hidden > 0 ? p.hidden : kHeadDim;
+    const int chw = small_chw(n_tokens);
     const size_t words = (kSmThreads / 256) * static_cast<size_t>(act_dim) + static_cast<size_t>(p.G) * p.W + p.W + 2 * p.G + kSmWaves +
                          static_cast<size_t>(p.G) * (p.L + 2) * kSmRep + 2 * static_cast<size_t>(kSmThreads) * chw +
                          2 * kSmWaves + static_cast<size_t>(kSmWaves) * kHeadDim;
-    return words * 4;
+    return words * 4 + (cache_bins ? static_cast<size_t>(p.G) * small_n_pad(n_tokens) * 2 : 0);
 }
 
 // The launch for one (key / value type, weight type) pair; step_small_bf16w.hip and
