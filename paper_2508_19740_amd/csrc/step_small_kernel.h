@@ -23,8 +23,8 @@
 // k tokens in (bin, token) order either way); the attention output differs in summation order only.
 //
 // Measured, it does NOT pay on this chip beyond a few thousand tokens per head, which is why the path
-// is an option that is off by default: one compute unit streams about 113 GB/s, so a head of 32768
-// tokens x 16 bytes costs 4.6 us per pass where the general path spreads it over eight compute units.
+// is an option that is off by default: one compute unit streams about 85 GB/s, so a head of 32768
+// tokens x 16 bytes costs 6 us per pass where the general path spreads it over eight compute units.
 // Batch 1, 32 heads, top-k 2 %: 32768 tokens 46 us as one launch (dispatch 4, hash 8, count 14, bound
 // + select 9, attend 10) against 27 us as five; 16384 tokens 31 against 25; 8192 tokens 25.0 against
 // 24.1; 4096 tokens 22.3 against 23.7; 2048 tokens 21.0 against 23.8.
