@@ -206,6 +206,25 @@ def measure(cfg, args, steps, warmup, with_graph=True, calibrate_copy=False, hot
     profile_enable(False)
     stage_us = {name: (ms * 1e3 / n if n else None) for name, (ms, n) in stage.items()}
 
+    # ------------------------------------------------------------------ retrieval calls back to back
+    # The same retrieve_topk calls with nothing between them (no append, no attention, no per-call
+    # events): what a stream of retrievals costs per call, without the two event records that
+    # bracket each call above.
+    def retrieve_only(i):
+        lay = layers[i % n_layers]
+        lay["ctx"].retrieve_topk(lay["q"], *lay["weights"], lay["codes"], N, k, out_idx=lay["idx"])
+
+    for i in range(warmup):
+        retrieve_only(i)
+    b2b = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    b2b[0].record()
+    for i in range(steps):
+        retrieve_only(i)
+    b2b[1].record()
+    torch.cuda.synchronize()
+    retrieve_b2b_us = b2b[0].elapsed_time(b2b[1]) * 1e3 / steps
+
     # ------------------------------------------------------------------ codes that fit the last-level cache
     hot_us = None
     if hot_cache:
@@ -272,7 +291,7 @@ def measure(cfg, args, steps, warmup, with_graph=True, calibrate_copy=False, hot
     res = {
         "cfg": cfg, "n_layers": n_layers, "esz": esz, "ms_per_step": ms_per_step,
         "retr_us": retr_us, "att_us": att_us, "retrieve_us": retrieve_us, "attend_us": attend_us,
-        "stage_us": stage_us, "hot_us": hot_us, "fused_ms": fused_ms_per_step, "graph_ms": graph_ms_per_step,
+        "stage_us": stage_us, "hot_us": hot_us, "retrieve_b2b_us": retrieve_b2b_us, "fused_ms": fused_ms_per_step, "graph_ms": graph_ms_per_step,
         "bulk_ms": bulk_ms, "t_gen": t_gen, "score_bytes": score_bytes, "retrieve_bytes": retrieve_bytes,
         "attend_bytes": attend_bytes,
         "bulk_gflops": 2.0 * B * Hkv * N * (cfg.hidden * d + L * cfg.hidden if cfg.hidden else L * d) / (bulk_ms * 1e-3) / 1e9,
@@ -379,6 +398,7 @@ def main():
         "library_build_id": sp.build_id(),
         "retrieve_us": {"mean": round(m["retrieve_us"], 2), "median": round(m["retr_us"][K_steps // 2], 2),
                         "min": round(m["retr_us"][0], 2)},
+        "retrieve_us_back_to_back": round(m["retrieve_b2b_us"], 2),
         "retrieve_us_hot_cache": None if m["hot_us"] is None else round(m["hot_us"], 2),
         "hot_cache_note": "same call with ONE layer, so the code stream can stay in the 256 MB last-level cache; "
                           "not an HBM number and not compared with the roofline",
@@ -416,6 +436,7 @@ def main():
             "steps": args.other_steps,
             "layers_rotated": o["n_layers"],
             "retrieve_us": round(o["retrieve_us"], 2),
+            "retrieve_us_back_to_back": round(o["retrieve_b2b_us"], 2),
             "attend_us": round(o["attend_us"], 2),
             "decode_step_one_call_ms": round(o["fused_ms"], 4),
             "kernel_us": {kname: (round(v, 2) if v is not None else None) for kname, v in su.items()},
