@@ -79,7 +79,7 @@ enum {
 
 typedef struct {
     int32_t batch;        /* B  >= 1                                                     */
-    int32_t n_q_heads;    /* Hq >= 1, multiple of n_kv_heads, Hq / Hkv <= 8              */
+    int32_t n_q_heads;    /* Hq >= 1, multiple of n_kv_heads, Hq / Hkv in 1 .. 8         */
     int32_t n_kv_heads;   /* Hkv >= 1                                                    */
     int32_t head_dim;     /* d; only 128 is supported                                    */
     int32_t code_bits;    /* L; multiple of 32 in [32, 512], or 1024 (then Hq / Hkv <= 2)   */

@@ -23,7 +23,7 @@ int make_plan(const spotlight_config* c, Plan* p)
         return SPOTLIGHT_ERR_INVALID_ARG;
     if (c->head_dim != kHeadDim) return SPOTLIGHT_ERR_UNSUPPORTED;
     const int G = c->n_q_heads / c->n_kv_heads;
-    if (G != 1 && G != 2 && G != 4 && G != 8) return SPOTLIGHT_ERR_UNSUPPORTED;
+    if (G > kMaxGroup) return SPOTLIGHT_ERR_UNSUPPORTED;
     // code lengths: every multiple of 32 up to 512 bits, and 1024 bits with at most two query heads per kv head
     if (c->code_bits > 512 && (c->code_bits != 1024 || G > 2)) return SPOTLIGHT_ERR_UNSUPPORTED;
     if (c->hidden % 8 != 0) return SPOTLIGHT_ERR_UNSUPPORTED;

@@ -772,13 +772,14 @@ int launch_w(spotlight_ctx* ctx, const RetrieveArgs& a)
         switch (p.G) {
         case 1: rc = launch_score_wg<W, 1>(ctx, timer, a, &tasks_per_group); break;
         case 2: rc = launch_score_wg<W, 2>(ctx, timer, a, &tasks_per_group); break;
-        case 4:
-            // 1024-bit codes: the histograms of more than two heads do not fit in LDS
-            if constexpr (W <= 16) { rc = launch_score_wg<W, 4>(ctx, timer, a, &tasks_per_group); break; }
+        // groups of three to eight heads; with 1024-bit codes their histograms do not fit in LDS
+#define SPOTLIGHT_SCORE_GROUP(GG)                                                                          \
+        case GG:                                                                                           \
+            if constexpr (W <= 16) { rc = launch_score_wg<W, GG>(ctx, timer, a, &tasks_per_group); break; } \
             return SPOTLIGHT_ERR_UNSUPPORTED;
-        case 8:
-            if constexpr (W <= 16) { rc = launch_score_wg<W, 8>(ctx, timer, a, &tasks_per_group); break; }
-            return SPOTLIGHT_ERR_UNSUPPORTED;
+        SPOTLIGHT_SCORE_GROUP(3) SPOTLIGHT_SCORE_GROUP(4) SPOTLIGHT_SCORE_GROUP(5) SPOTLIGHT_SCORE_GROUP(6)
+        SPOTLIGHT_SCORE_GROUP(7) SPOTLIGHT_SCORE_GROUP(8)
+#undef SPOTLIGHT_SCORE_GROUP
         default: return SPOTLIGHT_ERR_UNSUPPORTED;
         }
         if (rc != SPOTLIGHT_OK) return rc;

@@ -64,7 +64,7 @@ def test_validate_config_accepts_the_five_workloads():
     (dict(max_topk=0), sp.ERR_INVALID_ARG),
     (dict(max_topk=5000), sp.ERR_INVALID_ARG),                   # larger than max_tokens
     (dict(head_dim=64), sp.ERR_UNSUPPORTED),
-    (dict(n_q_heads=48, n_kv_heads=16), sp.ERR_UNSUPPORTED),     # group of 3
+    (dict(n_q_heads=36, n_kv_heads=4), sp.ERR_UNSUPPORTED),      # group of 9
     (dict(hidden=100), sp.ERR_UNSUPPORTED),                      # not a multiple of 8
 ])
 def test_validate_config_rejects(kw, rc):

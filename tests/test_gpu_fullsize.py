@@ -271,6 +271,20 @@ def test_c4_gqa_batch16():
         big.close()
 
 
+def test_groups_of_seven_at_128k_tokens():
+    """Qwen2.5-7B's attention layout (28 query heads on 4 key-value heads) at a 128K context: every
+    head through the whole chain on both sides."""
+    big = Big(wl.CONFIGS["Q7-128K"])
+    try:
+        c = big.cfg
+        idx = check_sampled_heads_real_chain(big, [(0, h) for h in range(c.n_kv_heads)], distances=True)
+        check_attention_all_heads(big, idx)
+        big.ctx.prepack_weights(*big.weights)
+        check_decode_step_on_synthetic_codes(big)
+    finally:
+        big.close()
+
+
 @pytest.mark.parametrize("words", [2, 5])
 def test_many_blocks_of_many_heads(words):
     """512 query heads x 9 token blocks: more (head, block) pairs than the chip holds at once, which

@@ -17,7 +17,7 @@ ATTN_TOL = 2e-3
 
 def draw(seed):
     r = random.Random(seed)
-    group = r.choice([1, 1, 2, 4, 8])
+    group = r.choice([1, 1, 2, 3, 4, 5, 6, 7, 8])
     n_kv = r.choice([1, 2, 3, 5])
     words = r.choice([1, 2, 3, 4, 4, 5, 7, 8, 8, 12, 16, 32]) if group <= 2 else r.choice([1, 2, 4, 4, 6, 8, 8, 11, 16])
     hidden = r.choice([0, 8, 64, 128, 128, 256, 384])

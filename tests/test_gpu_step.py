@@ -31,6 +31,8 @@ SMALL = {
                                           code_bits=64, needles=1),
     "many_vectors_lin": C["C4"].scaled(batch=9, n_q_heads=32, n_kv_heads=16, n_tokens=400 + 1, topk=75, hidden=0,
                                        code_bits=128, needles=1),
+    # 28 query heads on 4 key-value heads (groups of seven), the head layout of Qwen2.5-7B
+    "g7": C["C4"].scaled(batch=1, n_q_heads=28, n_kv_heads=4, n_tokens=6000 + 7, topk=150, code_bits=128, hidden=256, needles=1),
     # the two mixed pairings of key / value and weight element types
     "f32_kv_bf16_w": C["C1"].scaled(n_tokens=777, topk=77, weight_dtype="bf16", needles=2),
     "bf16_kv_f32_w": C["C2"].scaled(n_q_heads=2, n_kv_heads=2, n_tokens=1900, topk=90, weight_dtype="f32", needles=2),
@@ -42,7 +44,7 @@ FORCED = [(0, 0), (4, 64), (0, 1), (7, 0)]
 # cases the single-launch step serves (codes of at most 256 bits, hidden width a multiple of 128):
 # they run both ways, as one kernel and as the five kernels of the general path
 ONE_LAUNCH = {"c1", "c2_ragged", "c4_gqa", "lin_128", "block_edge", "g8", "many_vectors", "many_vectors_ragged",
-              "many_vectors_lin", "long_40k", "long_64k", "f32_kv_bf16_w", "bf16_kv_f32_w"}
+              "many_vectors_lin", "long_40k", "long_64k", "f32_kv_bf16_w", "bf16_kv_f32_w", "g7"}
 PARAMS = [(name, False) for name in sorted(SMALL)] + [(name, True) for name in sorted(ONE_LAUNCH)]
 
 

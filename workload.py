@@ -167,6 +167,10 @@ CONFIGS: Dict[str, Config] = {
     "C5-128": _cfg(5, name="C5-128", batch=4, n_q_heads=32, n_kv_heads=32, n_tokens=1048576,
                    code_bits=128, hidden=256, topk=10486, kv_dtype="bf16", weight_dtype="bf16",
                    needles=8, extra_tokens=64),
+    # Not one of the five: the attention layout of Qwen2.5-7B (28 query heads on 4 key-value heads,
+    # groups of seven), the model of the paper's efficiency experiments, at its 128K context.
+    "Q7-128K": _cfg(7, name="Q7-128K", batch=1, n_q_heads=28, n_kv_heads=4, n_tokens=131072,
+                    code_bits=128, hidden=256, topk=2622, kv_dtype="bf16", weight_dtype="bf16", needles=4),
 }
 
 
