@@ -15,6 +15,12 @@ def pytest_configure(config):
     __graft_entry__.ensure_built()
 
 
+def pytest_report_header(config):
+    """The library under test: the hash of the sources it was compiled from (and of the tree's)."""
+    from paper_2508_19740_amd import build as hip_build
+    return f"libspotlight build id {hip_build.built_id()} (sources in the tree: {hip_build.source_id()})"
+
+
 def pytest_collection_modifyitems(config, items):
     # GPU tests are skipped, not failed, on a machine without a GPU when selected by accident.
     try:
